@@ -1,0 +1,216 @@
+"""Seeded synthetic workloads shaped like the optimizer step of LLM fine-tuning.
+
+Only input generation lives here: shapes, value distributions, seeds and the places where
+inf/NaN patterns are planted.  None of the step's arithmetic (no scan, no update, no
+rounding rule of the method) is in this module; the only casts are the library casts that
+produce the low-precision *inputs*.  Both the GPU tests and the CPU oracle tests draw their
+inputs from here, so that the two sides see the same arrays.
+
+The step is element-wise, so only element counts, tensor boundaries and value scales
+matter; the shapes below stand in for the models the paper fine-tunes (Sec. VI-A lists
+Llama3.1-8B and Qwen2.5-7B/14B/32B).
+"""
+from dataclasses import dataclass, field
+from typing import List, Optional, Tuple
+
+import torch
+
+_TORCH_LP = {"bf16": torch.bfloat16, "f16": torch.float16}
+
+# 16-bit non-finite patterns planted by the overflow variants: +inf, -inf, quiet NaN,
+# signalling-NaN pattern, negative NaN.
+NONFINITE_BITS = {
+    "f16": (0x7C00, 0xFC00, 0x7E00, 0x7D01, 0xFE00),
+    "bf16": (0x7F80, 0xFF80, 0x7FC0, 0x7FA1, 0xFFC0),
+}
+
+
+@dataclass
+class FlatConfig:
+    """One flat sub-group."""
+    name: str
+    n: int
+    seed: int = 0
+    p_std: float = 0.02
+    m_std: float = 0.0        # 0 -> zeros
+    v_std: float = 0.0        # 0 -> zeros, else |N(0, v_std)|
+    g_std: float = 1e-3
+    gdt: str = "bf16"
+    pdt: str = "bf16"
+    loss_scale: float = 1.0
+    step: int = 1
+    max_norm: float = 0.0     # <= 0: no clipping
+    n_inject: int = 0         # number of planted inf/NaN entries
+    lr: float = 1e-5
+    beta1: float = 0.9
+    beta2: float = 0.999
+    eps: float = 1e-8
+    weight_decay: float = 0.01
+
+
+def config(name: str) -> FlatConfig:
+    """The flat configurations of the benchmark definition."""
+    table = {
+        "c1": FlatConfig("c1", 1 << 20, seed=0),
+        "c2": FlatConfig("c2", 100_000_000, seed=1, m_std=1e-4, v_std=1e-8, step=100,
+                         max_norm=1.0),
+        "c3a": FlatConfig("c3a", 50_000_000, seed=2, m_std=1e-4, v_std=1e-8, step=100,
+                          gdt="f16", loss_scale=65536.0, max_norm=1.0),
+        "c3b": FlatConfig("c3b", 50_000_000, seed=2, m_std=1e-4, v_std=1e-8, step=100,
+                          gdt="f16", loss_scale=65536.0, max_norm=1.0, n_inject=17),
+    }
+    return table[name]
+
+
+@dataclass
+class FlatState:
+    p: torch.Tensor
+    m: torch.Tensor
+    v: torch.Tensor
+    g: torch.Tensor           # low-precision gradient, already multiplied by loss_scale
+    p_lp: torch.Tensor
+    inject_idx: List[int] = field(default_factory=list)
+
+
+def _fill_normal(buf: torch.Tensor, std: float, gen: torch.Generator, piece: int = 1 << 27):
+    """In-place N(0, std) in bounded pieces (no full-size temporaries)."""
+    n = buf.numel()
+    for a in range(0, n, piece):
+        buf[a:min(n, a + piece)].normal_(0.0, std, generator=gen)
+
+
+def _fill_grad(g: torch.Tensor, std: float, scale: float, gen: torch.Generator,
+               piece: int = 1 << 27):
+    n = g.numel()
+    for a in range(0, n, piece):
+        b = min(n, a + piece)
+        tmp = torch.empty(b - a, dtype=torch.float32, device=g.device)
+        tmp.normal_(0.0, std, generator=gen)
+        if scale != 1.0:
+            tmp.mul_(scale)
+        g[a:b].copy_(tmp)      # library cast to the gradient's storage type
+        del tmp
+
+
+def plant_nonfinite(g: torch.Tensor, gdt: str, count: int, seed: int) -> List[int]:
+    """Overwrite `count` seeded random entries of g with a seeded mix of inf/NaN patterns."""
+    cpu_gen = torch.Generator(device="cpu")
+    cpu_gen.manual_seed(seed + 7919)
+    seen, idx = set(), []
+    while len(idx) < count:
+        for i in torch.randint(0, g.numel(), (count,), generator=cpu_gen).tolist():
+            if i not in seen and len(idx) < count:
+                seen.add(i)
+                idx.append(i)
+    pats = NONFINITE_BITS[gdt]
+    which = torch.randint(0, len(pats), (count,), generator=cpu_gen)
+    raw = g.view(torch.int16)
+    for k in range(count):
+        bits = pats[int(which[k])]
+        raw[int(idx[k])] = bits - 0x10000 if bits >= 0x8000 else bits
+    return idx
+
+
+def make_flat(cfg: FlatConfig, device: str = "cpu", n: Optional[int] = None) -> FlatState:
+    """Allocate and fill one flat sub-group on `device` (n overrides cfg.n for small cases)."""
+    n = cfg.n if n is None else n
+    gen = torch.Generator(device=device)
+    gen.manual_seed(cfg.seed)
+    p = torch.empty(n, dtype=torch.float32, device=device)
+    _fill_normal(p, cfg.p_std, gen)
+    m = torch.zeros(n, dtype=torch.float32, device=device)
+    if cfg.m_std > 0:
+        _fill_normal(m, cfg.m_std, gen)
+    v = torch.zeros(n, dtype=torch.float32, device=device)
+    if cfg.v_std > 0:
+        _fill_normal(v, cfg.v_std, gen)
+        v.abs_()
+    g = torch.empty(n, dtype=_TORCH_LP[cfg.gdt], device=device)
+    _fill_grad(g, cfg.g_std, cfg.loss_scale, gen)
+    p_lp = p.to(_TORCH_LP[cfg.pdt])
+    st = FlatState(p, m, v, g, p_lp)
+    if cfg.n_inject > 0 and n > 0:
+        st.inject_idx = plant_nonfinite(g, cfg.gdt, min(cfg.n_inject, n), cfg.seed)
+    return st
+
+
+# ----------------------------------------------------------------------------------------
+# Tensor lists shaped like decoder-only LLMs (element counts only).
+# ----------------------------------------------------------------------------------------
+def decoder_shapes(hidden: int, intermediate: int, layers: int, kv_heads: int, head_dim: int,
+                   vocab: int) -> List[Tuple[str, int]]:
+    """(name, numel) for embedding, per-layer q/k/v/o, gate/up/down, two norm vectors, LM head."""
+    kv = kv_heads * head_dim
+    out = [("embed", vocab * hidden)]
+    for i in range(layers):
+        out += [
+            ("l%d.q" % i, hidden * hidden), ("l%d.k" % i, kv * hidden),
+            ("l%d.v" % i, kv * hidden), ("l%d.o" % i, hidden * hidden),
+            ("l%d.gate" % i, intermediate * hidden), ("l%d.up" % i, intermediate * hidden),
+            ("l%d.down" % i, hidden * intermediate),
+            ("l%d.norm1" % i, hidden), ("l%d.norm2" % i, hidden),
+        ]
+    out.append(("lm_head", vocab * hidden))
+    return out
+
+
+def llama3_8b_shapes() -> List[Tuple[str, int]]:
+    """290 tensors, 8,030,257,152 elements (hidden 4096, FFN 14336, 32 layers, 8 KV heads)."""
+    return decoder_shapes(4096, 14336, 32, 8, 128, 128256)
+
+
+def qwen14b_class_shapes() -> List[Tuple[str, int]]:
+    """362 tensors, 12,567,592,960 elements (hidden 5120, FFN 13824, 40 layers, 8 KV heads)."""
+    return decoder_shapes(5120, 13824, 40, 8, 128, 152064)
+
+
+def scaled_shapes(shapes: List[Tuple[str, int]], divisor: int, ragged: bool = True):
+    """A miniature of a tensor list: every numel divided by `divisor` (at least 1), optionally
+    nudged so that sizes are not multiples of the vector width (exercises ragged tails)."""
+    out = []
+    for k, (name, numel) in enumerate(shapes):
+        m = max(1, numel // divisor)
+        if ragged:
+            m += k % 7
+        out.append((name, m))
+    return out
+
+
+@dataclass
+class ListState:
+    names: List[str]
+    p: List[torch.Tensor]
+    m: List[torch.Tensor]
+    v: List[torch.Tensor]
+    g: List[torch.Tensor]
+    p_lp: List[torch.Tensor]
+    flat: Optional[FlatState] = None     # the one allocation the views are cut from
+
+    @property
+    def total(self) -> int:
+        return sum(t.numel() for t in self.p)
+
+
+def make_list(shapes: List[Tuple[str, int]], cfg: FlatConfig, device: str = "cpu",
+              align_elems: int = 64) -> ListState:
+    """Fill one flat allocation per state and cut per-tensor views from it.
+
+    Each tensor starts at a multiple of `align_elems` elements (as separately allocated
+    framework tensors would); align_elems=1 packs them back to back, which misaligns most
+    tensors when their sizes are ragged.
+    """
+    offs, total = [], 0
+    for _, numel in shapes:
+        total = (total + align_elems - 1) // align_elems * align_elems
+        offs.append(total)
+        total += numel
+    flat = make_flat(cfg, device=device, n=total)
+    cut = lambda buf: [buf[o:o + numel] for o, (_, numel) in zip(offs, shapes)]
+    return ListState([s[0] for s in shapes], cut(flat.p), cut(flat.m), cut(flat.v), cut(flat.g),
+                     cut(flat.p_lp), flat)
+
+
+def bits16(t: torch.Tensor):
+    """Raw 16-bit patterns of a bf16/fp16 tensor as a numpy uint16 array (host copy)."""
+    import numpy as np
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16).copy()
