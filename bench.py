@@ -1,0 +1,223 @@
+#!/usr/bin/env python3
+"""Benchmark of the optimizer-step hot path on one MI355X.
+
+One step = the whole path over one batch of synthetic state: gradient scan (overflow flag +
+sum of squares), device-side gate and clip, AdamW update of fp32 p/m/v with the low-precision
+parameter copy.  Inputs are resident in HBM before the timed region starts.  Prints ONE JSON
+line: whole-job Gparam/s, the HBM roofline of the dominant (update) kernel measured with
+stream events inside the timed region, and the CPU oracle timed on the host cores on a
+bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+Workloads: llama3_8b (default; 290-tensor Llama-3-8B-shaped list, 8.03e9 elements, bf16
+gradients, clip 1.0), flat_1e8, fp16_5e7, c1, qwen14b_4sub (12.57e9 elements as 4 flat
+sub-groups streamed on one stream).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+from paper_2505_23254_amd import synth  # noqa: E402
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+STEP_BYTES_PER_PARAM = 28.0    # update kernel: read p,m,v (12) + g (2), write p,m,v (12) + p_lp (2)
+SCAN_BYTES_PER_PARAM = 2.0     # scan kernel: read g
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Workload:
+    """Holds device state and enqueues one step; records (scan, update) event pairs."""
+
+    def __init__(self, name, ma):
+        self.name, self.ma = name, ma
+        self.ws = ma.workspace()
+        self.res = ma.new_result()
+        self.t = 100
+        self.events = []
+        if name == "llama3_8b":
+            cfg = synth.FlatConfig(name, 0, seed=3, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
+            self.cfg = cfg
+            self.state = synth.make_list(synth.llama3_8b_shapes(), cfg, device="cuda")
+            self.plan = ma.MultiPlan(self.state.p, self.state.m, self.state.v, self.state.g,
+                                     self.state.p_lp)
+            self.n = self.plan.total
+            self.kind = "multi"
+            self.desc = ("290-tensor Llama-3-8B-shaped list, %d elements, fp32 p/m/v, bf16 grads "
+                         "~N(0,1e-3), clip 1.0" % self.n)
+        elif name == "qwen14b_4sub":
+            cfg = synth.FlatConfig(name, 0, seed=4, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
+            self.cfg = cfg
+            total = sum(n for _, n in synth.qwen14b_class_shapes())
+            self.flat = synth.make_flat(cfg, device="cuda", n=total)
+            self.n = total
+            self.kind = "sub"
+            self.parts = ma.new_result(4)
+            self.desc = ("14B-class list (%d elements) as 4 equal flat sub-groups streamed on one "
+                         "stream, bf16 grads, clip 1.0" % total)
+        else:
+            cfg = synth.config({"flat_1e8": "c2", "fp16_5e7": "c3a", "c1": "c1"}[name])
+            self.cfg = cfg
+            self.flat = synth.make_flat(cfg, device="cuda")
+            self.n = cfg.n
+            self.t = cfg.step
+            self.kind = "flat"
+            self.desc = "flat sub-group n=%d, %s grads, loss_scale %g, max_norm %g" % (
+                cfg.n, cfg.gdt, cfg.loss_scale, cfg.max_norm)
+        c = self.cfg
+        self.h = ma.hyper(c.lr, c.beta1, c.beta2, c.eps, c.weight_decay, 1)
+
+    def step(self, record):
+        ma, c = self.ma, self.cfg
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)] if record else None
+        if record:
+            ev[0].record()
+        if self.kind == "multi":
+            ma.multi_overflow_norm(self.plan, c.loss_scale, self.res, self.ws)
+            if record:
+                ev[1].record()
+            ma.multi_adamw_step_gated(self.plan, self.h, self.t, c.loss_scale, self.res, c.max_norm)
+        elif self.kind == "flat":
+            f = self.flat
+            ma.overflow_norm(f.g, c.loss_scale, self.res, self.ws)
+            if record:
+                ev[1].record()
+            ma.adamw_step_gated(f.p, f.m, f.v, f.g, f.p_lp, self.h, self.t, c.loss_scale, self.res,
+                                c.max_norm)
+        else:
+            f, sub = self.flat, self.n // 4
+            for k in range(4):
+                ma.overflow_norm(f.g[k * sub:(k + 1) * sub], c.loss_scale, self.parts, self.ws, index=k)
+            ma.norm_combine(self.parts, 4, self.res)
+            if record:
+                ev[1].record()
+            for k in range(4):
+                s = slice(k * sub, (k + 1) * sub)
+                ma.adamw_step_gated(f.p[s], f.m[s], f.v[s], f.g[s], f.p_lp[s], self.h, self.t,
+                                    c.loss_scale, self.res, c.max_norm)
+        if record:
+            ev[2].record()
+            self.events.append(ev)
+        self.t += 1
+
+
+def cpu_baseline(wl, sample_elems, passes):
+    """The CPU oracle, as it stands, on the first `sample_elems` elements of the workload's state
+    (copied to the host), all host cores of this machine's share; also one thread on a smaller piece."""
+    import numpy as np
+    import oracle
+    c = wl.cfg
+    src = wl.state.flat if wl.kind == "multi" else wl.flat
+    n = min(sample_elems, src.p.numel())
+    p, m, v = (t[:n].cpu().numpy().copy() for t in (src.p, src.m, src.v))
+    g = synth.bits16(src.g[:n])
+    lp = synth.bits16(src.p_lp[:n])
+    h = oracle.hyper(c.lr, c.beta1, c.beta2, c.eps, c.weight_decay, 1)
+    cores = min(16, os.cpu_count() or 1)
+    try:
+        cores = min(cores, len(os.sched_getaffinity(0)))
+    except AttributeError:
+        pass
+    oracle.optimizer_step(p, m, v, g, c.gdt, lp, c.pdt, h, 100, c.loss_scale, c.max_norm, nthreads=cores)
+    t0 = time.perf_counter()
+    for k in range(passes):
+        oracle.optimizer_step(p, m, v, g, c.gdt, lp, c.pdt, h, 101 + k, c.loss_scale, c.max_norm,
+                              nthreads=cores)
+    dt = (time.perf_counter() - t0) / passes
+    n1 = min(n, 1 << 24)
+    t0 = time.perf_counter()
+    oracle.optimizer_step(p[:n1], m[:n1], v[:n1], g[:n1], c.gdt, lp[:n1], c.pdt, h, 200, c.loss_scale,
+                          c.max_norm, nthreads=1)
+    dt1 = time.perf_counter() - t0
+    return {
+        "value": n / dt / 1e9, "unit": "Gparam/s", "cores": cores, "kind": "oracle",
+        "sample": "first %d elements of the workload, %d full passes (scan+gate+update) over %d "
+                  "threads; single thread on %d elements: %.4f Gparam/s"
+                  % (n, passes, cores, n1, n1 / dt1 / 1e9),
+        "single_thread_value": n1 / dt1 / 1e9,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="llama3_8b",
+                    choices=["llama3_8b", "flat_1e8", "fp16_5e7", "c1", "qwen14b_4sub"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample", type=int, default=1 << 28)
+    ap.add_argument("--cpu-passes", type=int, default=4)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU's share of the optimizer step; "
+                 "--gpus must be 1 (no collectives or sharding are part of it)")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+
+    from paper_2505_23254_amd import binding as ma  # fails loudly if the library is not built
+
+    torch.cuda.set_device(0)
+    t_setup = time.perf_counter()
+    wl = Workload(args.workload, ma)
+    torch.cuda.synchronize()
+    log("setup %.1f s: %s" % (time.perf_counter() - t_setup, wl.desc))
+
+    for _ in range(args.warmup):
+        wl.step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        wl.step(True)
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    scan_ms = sum(e[0].elapsed_time(e[1]) for e in wl.events) / len(wl.events)
+    upd_ms = sum(e[1].elapsed_time(e[2]) for e in wl.events) / len(wl.events)
+    launches = 4 if wl.kind == "sub" else 1      # update launches per step
+    ov, ss = ma.read_result(wl.res)
+    if ov:
+        sys.exit("bench.py: unexpected overflow flag on clean synthetic gradients")
+    achieved = STEP_BYTES_PER_PARAM * wl.n / (upd_ms * 1e-3) / 1e9
+    out = {
+        "metric": "optimizer-step Gparam/s and achieved HBM GB/s (% of peak), 8B-shaped, 1 GPU",
+        "value": wl.n / (ms_per_step * 1e-3) / 1e9,
+        "unit": "Gparam/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": args.workload, "description": wl.desc, "elements": wl.n,
+                   "grad_dtype": wl.cfg.gdt, "param_copy_dtype": wl.cfg.pdt,
+                   "max_norm": wl.cfg.max_norm, "loss_scale": wl.cfg.loss_scale,
+                   "sumsq_last_step": ss},
+        "roofline": {
+            "bound": "hbm", "kernel": "AdamW update (+ low-precision copy)",
+            "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+            "bytes_per_param": STEP_BYTES_PER_PARAM, "params_per_launch": wl.n / launches,
+            "avg_launch_ms": upd_ms / launches,
+            "scan": {"avg_ms": scan_ms, "bytes_per_param": SCAN_BYTES_PER_PARAM,
+                     "achieved": SCAN_BYTES_PER_PARAM * wl.n / (scan_ms * 1e-3) / 1e9},
+            "whole_step_GBps": 30.0 * wl.n / (ms_per_step * 1e-3) / 1e9,
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample, args.cpu_passes)
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

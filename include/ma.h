@@ -1,0 +1,189 @@
+/*
+ * ma.h -- C ABI of the MI355X optimizer-step library (libma_step.so).
+ *
+ * The library runs, on one GPU, the per-sub-group optimizer step that an SSD-offloaded
+ * mixed-precision fine-tuning system executes once per iteration over its flat partitioned
+ * buffers (MemAscend, arXiv 2505.23254):
+ *
+ *   1. ma_overflow_norm      one pass over the gradient: overflow flag (any +inf, -inf or NaN;
+ *                            Sec. III-C, Sec. IV-D / Algorithm 1) fused with the sum of squares
+ *                            needed for global-norm clipping;
+ *   2. the gate              on overflow the step is skipped and every state stays bit-unchanged
+ *                            (Sec. III-C: the caller then lowers the loss scale); otherwise the
+ *                            clip coefficient follows from the norm;
+ *   3. ma_adamw_step         unscale + clip + AdamW with bias correction and decoupled weight
+ *                            decay on fp32 master p / m / v (Sec. II-A), and the low-precision
+ *                            copy of the new parameter written in the same pass (Sec. III-D lists
+ *                            the low-precision compute weights kept beside the fp32 masters).
+ *
+ * Conventions that hold for every entry point
+ *   - All data pointers are DEVICE pointers owned by the caller, unless the name ends in _host.
+ *     The library never allocates, frees or keeps device memory.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued on it; results are valid once the stream has been synchronised.  No entry point
+ *     synchronises the device, except ma_multi_prepare (documented there).
+ *   - Return value: MA_OK (0) or a negative ma_status.  On any error nothing has been launched
+ *     and no buffer has been written.  ma_last_error() returns a thread-local message.
+ *   - n is a size_t element count; sub-groups beyond 2^31 elements are supported.
+ *   - Buffers must not overlap each other.  Pointers must be aligned to their element size;
+ *     16-byte alignment of every buffer enables the 128-bit path, anything else is handled by a
+ *     scalar path with the same results.
+ */
+#ifndef MA_STEP_H_
+#define MA_STEP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ma_dtype {
+  MA_F32 = 0,  /* IEEE binary32 */
+  MA_BF16 = 1, /* upper 16 bits of binary32 */
+  MA_F16 = 2   /* IEEE binary16 */
+} ma_dtype;
+
+typedef enum ma_status {
+  MA_OK = 0,
+  MA_ERR_NULL = -1,  /* a required pointer is NULL */
+  MA_ERR_DTYPE = -2, /* dtype not supported in this position */
+  MA_ERR_ALIGN = -3, /* pointer not aligned to its element size */
+  MA_ERR_ARG = -4,   /* value out of range (see each call) or workspace too small */
+  MA_ERR_HIP = -5    /* the HIP runtime reported an error; text in ma_last_error() */
+} ma_status;
+
+/* Result of the gradient scan, 16 bytes, lives in device memory. */
+typedef struct ma_norm_result {
+  int32_t overflow; /* 1 if any element is +inf, -inf or NaN, else 0 */
+  int32_t reserved; /* written as 0 */
+  double sumsq;     /* sum over i of (g_i / loss_scale)^2; unspecified when overflow == 1 */
+} ma_norm_result;
+
+/* AdamW hyper-parameters (Sec. II-A: bias correction, decoupled weight decay). */
+typedef struct ma_hyper {
+  float lr;                /* >= 0 */
+  float beta1;             /* in [0, 1) */
+  float beta2;             /* in [0, 1) */
+  float eps;               /* > 0 */
+  float weight_decay;      /* >= 0; multiplies lr (decoupled decay) */
+  int32_t bias_correction; /* non-zero: divide by 1 - beta^step */
+} ma_hyper;
+
+/* One tensor of a multi-tensor step.  All five buffers hold n elements. */
+typedef struct ma_tensor {
+  float* p32;       /* fp32 master parameter, updated in place */
+  float* m;         /* fp32 first moment, updated in place */
+  float* v;         /* fp32 second moment, updated in place */
+  const void* grad; /* gradient in the list's gradient dtype, read only */
+  void* p_lp;       /* low-precision parameter copy, written */
+  size_t n;
+} ma_tensor;
+
+/* Host-side handle of a prepared tensor list (plain data, caller-owned, copyable). */
+typedef struct ma_multi_plan {
+  const void* table_dev; /* device table written by ma_multi_prepare */
+  uint64_t entries;      /* table rows (a misaligned tensor may take two) */
+  uint64_t total_elems;
+  uint64_t norm_chunks;  /* work items of the scan kernel */
+  uint64_t step_chunks;  /* work items of the update kernel */
+  int32_t gdt;
+  int32_t pdt;
+  uint32_t magic;
+  uint32_t reserved;
+} ma_multi_plan;
+
+/* ---- housekeeping ---------------------------------------------------------------------- */
+
+/* Library version, major*10000 + minor*100 + patch. */
+int ma_version(void);
+
+/* Message of the last failing call on this thread ("" if none).  Static storage. */
+const char* ma_last_error(void);
+
+/* Bytes of device workspace ma_overflow_norm / ma_multi_overflow_norm need (per-block partial
+ * results of the two-level reduction).  Independent of n.  The workspace may be reused by
+ * later calls on the same stream; calls on different streams need different workspaces. */
+size_t ma_workspace_bytes(void);
+
+/* Host helper: the clip coefficient of global-norm clipping,
+ *   c = min(1, max_norm / (sqrt(sumsq) + 1e-6)),  evaluated in fp64, rounded once to fp32;
+ * max_norm <= 0 disables clipping (c = 1). */
+float ma_clip_coef(double sumsq, float max_norm);
+
+/* ---- step 1: overflow scan fused with the sum of squares ---------------------------------- */
+
+/* Scans grad[0..n) (dtype gdt: MA_BF16, MA_F16 or MA_F32) once.
+ *   out_dev->overflow  Algorithm 1 (Sec. IV-D): 1 iff some element has an all-ones exponent
+ *                      (+inf, -inf, NaN), tested on the raw stored pattern.  No early exit: the
+ *                      same pass also needs the full sum.
+ *   out_dev->sumsq     sum of (g_i / loss_scale)^2, accumulated in fp64 with a fixed reduction
+ *                      order (bit-identical from run to run on the same device).
+ * loss_scale must be finite and > 0.  n == 0 writes {0, 0.0}.
+ * ws: device workspace of at least ma_workspace_bytes(). */
+int ma_overflow_norm(const void* grad, ma_dtype gdt, size_t n, float loss_scale,
+                     ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream);
+
+/* Adds up `count` scan results (e.g. one per sub-group streamed through the optimizer-state
+ * buffer, Sec. IV-C) in index order: overflow = OR, sumsq = fp64 sum.  out_dev may be one of
+ * the inputs' neighbours but not an element of parts_dev.  count >= 1. */
+int ma_norm_combine(const ma_norm_result* parts_dev, size_t count, ma_norm_result* out_dev,
+                    void* stream);
+
+/* ---- step 3: unscale + clip + AdamW + low-precision copy -------------------------------------- */
+
+/* One AdamW step (1-based `step`) over a flat sub-group of n elements, in fp32:
+ *     g    = widen(grad_i) * fl32(clip_coef / loss_scale)
+ *     m'   = beta1*m + (1-beta1)*g
+ *     v'   = beta2*v + (1-beta2)*g*g
+ *     p'   = (p - lr*wd*p) - (lr / (1-beta1^step)) * m' / (sqrt(v') / sqrt(1-beta2^step) + eps)
+ *     p_lp = round-to-nearest-even(p') in dtype pdt (MA_BF16 or MA_F16)
+ * p32, m, v are updated in place; p_lp is written; grad (MA_BF16, MA_F16 or MA_F32) is read.
+ * p_lp may be NULL (no low-precision copy is written; pdt is ignored).
+ * Requirements: step >= 1, loss_scale finite > 0, 0 < clip_coef <= 1, hyper ranges as in
+ * ma_hyper.  This entry point does not look at the overflow flag: the caller gates. */
+int ma_adamw_step(float* p32, float* m, float* v, const void* grad, ma_dtype gdt, void* p_lp,
+                  ma_dtype pdt, size_t n, const ma_hyper* hyper, int64_t step, float loss_scale,
+                  float clip_coef, void* stream);
+
+/* The same step with the gate of Sec. III-C taken on the device, so that scan and update can be
+ * enqueued back to back without a host round trip: the kernel reads *gate_dev (written earlier on
+ * the same stream by ma_overflow_norm / ma_norm_combine); if gate_dev->overflow != 0 it returns
+ * without touching any buffer; otherwise it derives clip_coef from gate_dev->sumsq and max_norm
+ * exactly as ma_clip_coef does (max_norm <= 0: no clipping). */
+int ma_adamw_step_gated(float* p32, float* m, float* v, const void* grad, ma_dtype gdt, void* p_lp,
+                        ma_dtype pdt, size_t n, const ma_hyper* hyper, int64_t step,
+                        float loss_scale, const ma_norm_result* gate_dev, float max_norm,
+                        void* stream);
+
+/* ---- multi-tensor variants (one launch over a whole tensor list) ------------------------------ */
+
+/* Bytes of device memory ma_multi_prepare needs for a list of `count` tensors. */
+size_t ma_multi_table_bytes(size_t count);
+
+/* Validates list_host[0..count) (host array of device pointers; gradient dtype gdt, parameter
+ * copy dtype pdt for the whole list), builds the work table and copies it to table_dev.  This
+ * call synchronises `stream` before it returns, so list_host may be freed at once and the table
+ * may be used on any stream afterwards.  Prepare once per tensor list; the plan stays valid as
+ * long as the tensors do not move.  Tensors with n == 0 are allowed and skipped.  count >= 1. */
+int ma_multi_prepare(const ma_tensor* list_host, size_t count, ma_dtype gdt, ma_dtype pdt,
+                     void* table_dev, size_t table_bytes, void* stream, ma_multi_plan* plan_out);
+
+/* ma_overflow_norm over every tensor of the plan: one flag, one sum. */
+int ma_multi_overflow_norm(const ma_multi_plan* plan, float loss_scale, ma_norm_result* out_dev,
+                           void* ws, size_t ws_bytes, void* stream);
+
+/* ma_adamw_step over every tensor of the plan (same scalars for all tensors). */
+int ma_multi_adamw_step(const ma_multi_plan* plan, const ma_hyper* hyper, int64_t step,
+                        float loss_scale, float clip_coef, void* stream);
+
+/* ma_adamw_step_gated over every tensor of the plan. */
+int ma_multi_adamw_step_gated(const ma_multi_plan* plan, const ma_hyper* hyper, int64_t step,
+                              float loss_scale, const ma_norm_result* gate_dev, float max_norm,
+                              void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MA_STEP_H_ */

@@ -1,0 +1,225 @@
+"""ctypes binding of libma_step.so (C ABI in include/ma.h).
+
+Argument marshalling only: every step of the path runs in the library's HIP kernels.  torch is
+used for device memory and the current HIP stream.  Importing this module fails loudly when the
+library has not been built (python -m paper_2505_23254_amd.build, or __graft_entry__.build()).
+"""
+import ctypes
+import os
+import struct
+from typing import List, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libma_step.so")
+
+MA_F32, MA_BF16, MA_F16 = 0, 1, 2
+_DT = {torch.float32: MA_F32, torch.bfloat16: MA_BF16, torch.float16: MA_F16}
+
+MA_OK, MA_ERR_NULL, MA_ERR_DTYPE, MA_ERR_ALIGN, MA_ERR_ARG, MA_ERR_HIP = 0, -1, -2, -3, -4, -5
+
+
+class MaError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__("libma_step error %d: %s" % (code, message))
+        self.code = code
+
+
+class Hyper(ctypes.Structure):
+    _fields_ = [("lr", ctypes.c_float), ("beta1", ctypes.c_float), ("beta2", ctypes.c_float),
+                ("eps", ctypes.c_float), ("weight_decay", ctypes.c_float),
+                ("bias_correction", ctypes.c_int32)]
+
+
+class Tensor(ctypes.Structure):
+    _fields_ = [("p32", ctypes.c_void_p), ("m", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("grad", ctypes.c_void_p), ("p_lp", ctypes.c_void_p), ("n", ctypes.c_size_t)]
+
+
+class MultiPlanStruct(ctypes.Structure):
+    _fields_ = [("table_dev", ctypes.c_void_p), ("entries", ctypes.c_uint64),
+                ("total_elems", ctypes.c_uint64), ("norm_chunks", ctypes.c_uint64),
+                ("step_chunks", ctypes.c_uint64), ("gdt", ctypes.c_int32), ("pdt", ctypes.c_int32),
+                ("magic", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            "%s is missing: build it first (python -m paper_2505_23254_amd.build). "
+            "There is no fallback path." % LIB_PATH)
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, sz, i32, i64, f32, f64 = (ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32,
+                                  ctypes.c_int64, ctypes.c_float, ctypes.c_double)
+    sig = {
+        "ma_version": ([], ctypes.c_int),
+        "ma_last_error": ([], ctypes.c_char_p),
+        "ma_workspace_bytes": ([], sz),
+        "ma_clip_coef": ([f64, f32], f32),
+        "ma_overflow_norm": ([vp, i32, sz, f32, vp, vp, sz, vp], ctypes.c_int),
+        "ma_norm_combine": ([vp, sz, vp, vp], ctypes.c_int),
+        "ma_adamw_step": ([vp, vp, vp, vp, i32, vp, i32, sz, vp, i64, f32, f32, vp], ctypes.c_int),
+        "ma_adamw_step_gated": ([vp, vp, vp, vp, i32, vp, i32, sz, vp, i64, f32, vp, f32, vp],
+                                ctypes.c_int),
+        "ma_multi_table_bytes": ([sz], sz),
+        "ma_multi_prepare": ([vp, sz, i32, i32, vp, sz, vp, vp], ctypes.c_int),
+        "ma_multi_overflow_norm": ([vp, f32, vp, vp, sz, vp], ctypes.c_int),
+        "ma_multi_adamw_step": ([vp, vp, i64, f32, f32, vp], ctypes.c_int),
+        "ma_multi_adamw_step_gated": ([vp, vp, i64, f32, vp, f32, vp], ctypes.c_int),
+    }
+    for name, (args, res) in sig.items():
+        fn = getattr(lib, name)
+        fn.argtypes = args
+        fn.restype = res
+    return lib
+
+
+lib = _load()
+
+
+def _check(rc: int):
+    if rc != MA_OK:
+        raise MaError(rc, lib.ma_last_error().decode())
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _dev(t: Optional[torch.Tensor], name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise TypeError("%s must live on the GPU" % name)
+    if not t.is_contiguous():
+        raise TypeError("%s must be contiguous" % name)
+    return t.data_ptr()
+
+
+def hyper(lr=1e-5, beta1=0.9, beta2=0.999, eps=1e-8, weight_decay=0.01, bias_correction=1) -> Hyper:
+    return Hyper(lr, beta1, beta2, eps, weight_decay, int(bias_correction))
+
+
+def version() -> int:
+    return lib.ma_version()
+
+
+def clip_coef(sumsq: float, max_norm: float) -> float:
+    return lib.ma_clip_coef(float(sumsq), float(max_norm))
+
+
+def workspace(device="cuda") -> torch.Tensor:
+    """Device workspace for the scan calls (per-block partials)."""
+    return torch.empty(lib.ma_workspace_bytes(), dtype=torch.uint8, device=device)
+
+
+def new_result(count: int = 1, device="cuda") -> torch.Tensor:
+    """`count` ma_norm_result slots (16 bytes each) as a float64 tensor of 2*count."""
+    return torch.zeros(2 * count, dtype=torch.float64, device=device)
+
+
+def read_result(res: torch.Tensor, index: int = 0):
+    """Synchronising read-back of one ma_norm_result: (overflow: bool, sumsq: float)."""
+    raw = res[2 * index:2 * index + 2].cpu().numpy().tobytes()
+    ov, _, ss = struct.unpack("<iid", raw)
+    return bool(ov), ss
+
+
+def _slot(res: torch.Tensor, index: int) -> int:
+    if res.dtype != torch.float64 or res.numel() < 2 * (index + 1):
+        raise TypeError("result buffer must come from new_result()")
+    return _dev(res, "result") + 16 * index
+
+
+def overflow_norm(grad: torch.Tensor, loss_scale: float, out: torch.Tensor, ws: torch.Tensor,
+                  index: int = 0, stream=None, n: Optional[int] = None) -> None:
+    """ma_overflow_norm: scan `grad`, write slot `index` of `out`."""
+    _check(lib.ma_overflow_norm(_dev(grad, "grad"), _DT[grad.dtype],
+                                grad.numel() if n is None else n, loss_scale, _slot(out, index),
+                                _dev(ws, "ws"), ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def norm_combine(parts: torch.Tensor, count: int, out: torch.Tensor, index: int = 0,
+                 stream=None) -> None:
+    _check(lib.ma_norm_combine(_slot(parts, 0), count, _slot(out, index), _stream(stream)))
+
+
+def _step_args(p, m, v, grad, p_lp):
+    for t, nm in ((p, "p32"), (m, "m"), (v, "v")):
+        if t.dtype != torch.float32:
+            raise TypeError("%s must be float32" % nm)
+    n = p.numel()
+    if not (m.numel() == n and v.numel() == n and grad.numel() == n and
+            (p_lp is None or p_lp.numel() == n)):
+        raise ValueError("p32, m, v, grad and p_lp must have the same number of elements")
+    pdt = _DT[p_lp.dtype] if p_lp is not None else MA_BF16
+    return (_dev(p, "p32"), _dev(m, "m"), _dev(v, "v"), _dev(grad, "grad"), _DT[grad.dtype],
+            _dev(p_lp, "p_lp"), pdt, n)
+
+
+def adamw_step(p, m, v, grad, p_lp, h: Hyper, step: int, loss_scale: float = 1.0,
+               clip: float = 1.0, stream=None) -> None:
+    """ma_adamw_step on one flat sub-group (caller has already taken the gate)."""
+    _check(lib.ma_adamw_step(*_step_args(p, m, v, grad, p_lp), ctypes.byref(h), int(step),
+                             loss_scale, clip, _stream(stream)))
+
+
+def adamw_step_gated(p, m, v, grad, p_lp, h: Hyper, step: int, loss_scale: float,
+                     gate: torch.Tensor, max_norm: float, index: int = 0, stream=None) -> None:
+    """ma_adamw_step_gated: the kernel reads slot `index` of `gate` on the device."""
+    _check(lib.ma_adamw_step_gated(*_step_args(p, m, v, grad, p_lp), ctypes.byref(h), int(step),
+                                   loss_scale, _slot(gate, index), max_norm, _stream(stream)))
+
+
+class MultiPlan:
+    """A prepared tensor list (ma_multi_prepare).  Keeps the device table and the tensors alive."""
+
+    def __init__(self, p: Sequence[torch.Tensor], m: Sequence[torch.Tensor],
+                 v: Sequence[torch.Tensor], grad: Sequence[torch.Tensor],
+                 p_lp: Optional[Sequence[torch.Tensor]], stream=None):
+        count = len(p)
+        if not (len(m) == count and len(v) == count and len(grad) == count and
+                (p_lp is None or len(p_lp) == count)) or count == 0:
+            raise ValueError("lists must be non-empty and of equal length")
+        gdt = _DT[grad[0].dtype]
+        pdt = _DT[p_lp[0].dtype] if p_lp is not None else MA_BF16
+        arr = (Tensor * count)()
+        for i in range(count):
+            lp = p_lp[i] if p_lp is not None else None
+            if _DT[grad[i].dtype] != gdt or (lp is not None and _DT[lp.dtype] != pdt):
+                raise TypeError("all tensors of a list share one gradient and one p_lp dtype")
+            pp, pm, pv, pg, _, pl, _, n = _step_args(p[i], m[i], v[i], grad[i], lp)
+            arr[i] = Tensor(pp, pm, pv, pg, pl, n)
+        self._keep = (list(p), list(m), list(v), list(grad), list(p_lp) if p_lp is not None else None)
+        self.table = torch.empty(lib.ma_multi_table_bytes(count), dtype=torch.uint8,
+                                 device=p[0].device)
+        self.plan = MultiPlanStruct()
+        _check(lib.ma_multi_prepare(arr, count, gdt, pdt, self.table.data_ptr(),
+                                    self.table.numel(), _stream(stream), ctypes.byref(self.plan)))
+
+    @property
+    def total(self) -> int:
+        return int(self.plan.total_elems)
+
+
+def multi_overflow_norm(plan: MultiPlan, loss_scale: float, out: torch.Tensor, ws: torch.Tensor,
+                        index: int = 0, stream=None) -> None:
+    _check(lib.ma_multi_overflow_norm(ctypes.byref(plan.plan), loss_scale, _slot(out, index),
+                                      _dev(ws, "ws"), ws.numel() * ws.element_size(),
+                                      _stream(stream)))
+
+
+def multi_adamw_step(plan: MultiPlan, h: Hyper, step: int, loss_scale: float = 1.0,
+                     clip: float = 1.0, stream=None) -> None:
+    _check(lib.ma_multi_adamw_step(ctypes.byref(plan.plan), ctypes.byref(h), int(step), loss_scale,
+                                   clip, _stream(stream)))
+
+
+def multi_adamw_step_gated(plan: MultiPlan, h: Hyper, step: int, loss_scale: float,
+                           gate: torch.Tensor, max_norm: float, index: int = 0,
+                           stream=None) -> None:
+    _check(lib.ma_multi_adamw_step_gated(ctypes.byref(plan.plan), ctypes.byref(h), int(step),
+                                         loss_scale, _slot(gate, index), max_norm, _stream(stream)))

@@ -1,0 +1,176 @@
+// Device-side building blocks shared by the scan and update kernels (gfx950, wave64).
+//
+// Everything here is written for streaming: each lane moves 128-bit (or 64-bit for 16-bit
+// operands of a 4-wide group) packets with non-temporal hints, one wave covers 1 KiB of
+// contiguous memory per load instruction, and nothing is re-read.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ma {
+
+constexpr int kBlock = 256;  // 4 waves of 64 lanes
+constexpr int kWave = 64;
+
+// dtype codes, numerically equal to ma_dtype in the public header
+constexpr int kF32 = 0;
+constexpr int kBF16 = 1;
+constexpr int kF16 = 2;
+constexpr int kNoLp = 3;  // update kernel variant that writes no low-precision copy
+
+#ifndef MA_NORM_UNROLL
+#define MA_NORM_UNROLL 4  // 16-byte loads in flight per lane in the scan kernel
+#endif
+#ifndef MA_STEP_UNROLL
+#define MA_STEP_UNROLL 2  // 4-element groups in flight per lane in the update kernel
+#endif
+
+constexpr int kNormUnroll = MA_NORM_UNROLL;
+constexpr int kStepUnroll = MA_STEP_UNROLL;
+constexpr uint64_t kNormChunkBytes = uint64_t(kBlock) * 16 * kNormUnroll;  // per work item
+constexpr uint64_t kStepChunkElems = uint64_t(kBlock) * 4 * kStepUnroll;   // per work item
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef unsigned short u16x2 __attribute__((ext_vector_type(2)));
+
+// One row of the work table: a tensor (or flat sub-group) and where its work items start.
+struct Desc {
+  float* p;
+  float* m;
+  float* v;
+  const void* g;
+  void* lp;
+  uint64_t n;
+  uint64_t norm_chunk0;  // index of this row's first scan work item
+  uint64_t step_chunk0;  // index of this row's first update work item
+  uint32_t norm_head;    // elements before the gradient's first 16-byte boundary
+  uint32_t step_head;    // elements before the common 4-element-group boundary
+  uint32_t step_vec;     // 1: the 4-wide path is usable after step_head elements
+  uint32_t pad;
+};
+static_assert(sizeof(Desc) == 80, "table row layout");
+
+// Scalars of one AdamW step, each rounded to fp32 once on the host (or in the gated prologue).
+struct StepScalars {
+  float beta1, beta2, omb1, omb2, eps, step_size, inv_sqrt_bc2, decay, gscale;
+};
+
+// Partial result of one block of the scan kernel.
+struct NormPartial {
+  double sum;
+  uint32_t maxabs;  // running maximum of the sign-stripped patterns (two 16-bit lanes, or one
+                    // 32-bit value for fp32 gradients)
+  uint32_t pad;
+};
+
+struct NormResult {  // same layout as ma_norm_result
+  int32_t overflow;
+  int32_t reserved;
+  double sumsq;
+};
+
+// ---- memory ------------------------------------------------------------------------------
+// Pointers read from a table in memory carry no address-space information, and the compiler
+// would fall back to flat addressing for them.  Every buffer of this library is global device
+// memory, so the kernels say so once and get global_load / global_store throughout.
+#define MA_GLOBAL __attribute__((address_space(1)))
+
+template <class T>
+__device__ __forceinline__ MA_GLOBAL T* to_global(T* p) {
+  return (MA_GLOBAL T*)p;
+}
+template <class T>
+__device__ __forceinline__ T ld_stream(MA_GLOBAL const T* p) {
+  return __builtin_nontemporal_load(p);
+}
+template <class T>
+__device__ __forceinline__ void st_stream(MA_GLOBAL T* p, T x) {
+  __builtin_nontemporal_store(x, p);
+}
+
+// ---- format conversion ----------------------------------------------------------------------
+__device__ __forceinline__ float bits_to_f32(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t f32_to_bits(float x) { return __builtin_bit_cast(uint32_t, x); }
+
+// Widen one 16-bit gradient pattern (in the low half of `h`) to fp32; exact for both formats.
+template <int DT>
+__device__ __forceinline__ float widen16(uint32_t h) {
+  if constexpr (DT == kBF16) {
+    return bits_to_f32(h << 16);
+  } else {
+    return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<unsigned short>(h)));
+  }
+}
+
+// Round fp32 to a 16-bit pattern, nearest-even.  NaN becomes a quiet NaN keeping the sign and
+// the top payload bits.
+template <int DT>
+__device__ __forceinline__ uint32_t narrow16(float x) {
+  const uint32_t b = f32_to_bits(x);
+  if constexpr (DT == kBF16) {
+    // add half an ulp of the kept part, plus the parity of the kept lsb minus one: ties land
+    // on the even neighbour and a carry may run into the exponent (up to infinity)
+    uint32_t r = (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+    if ((b & 0x7FFFFFFFu) > 0x7F800000u) r = (b >> 16) | 0x0040u;
+    return r;
+  } else {
+    // The empty asm pins x as an fp32 value in a register.  Without it the compiler merges the
+    // fma that produced x with this conversion into one mixed-precision fma that rounds the
+    // exact result straight to fp16, which differs from RNE(fp32 value) on halfway cases.
+    float y = x;
+    asm("" : "+v"(y));
+    uint32_t r = __builtin_bit_cast(unsigned short, static_cast<_Float16>(y));
+    if ((b & 0x7FFFFFFFu) > 0x7F800000u) {
+      r = ((b >> 16) & 0x8000u) | 0x7E00u | ((b >> 13) & 0x01FFu);
+    }
+    return r;
+  }
+}
+
+// ---- the update of one element ------------------------------------------------------------------
+// fp32 throughout; products, the quotient and the square root each round once, and every
+// addition is the tail of an fma (the translation unit is built with contraction off, so the
+// compiler adds no fusion of its own).
+__device__ __forceinline__ void adamw_element(const StepScalars& s, float g_raw, float& p, float& m,
+                                              float& v) {
+  const float g = g_raw * s.gscale;
+  const float m1 = __builtin_fmaf(s.beta1, m, s.omb1 * g);
+  const float v1 = __builtin_fmaf(s.beta2, v, s.omb2 * (g * g));
+  const float d = __builtin_fmaf(__builtin_sqrtf(v1), s.inv_sqrt_bc2, s.eps);
+  const float u = m1 / d;
+  const float q = __builtin_fmaf(-s.decay, p, p);
+  p = __builtin_fmaf(-s.step_size, u, q);
+  m = m1;
+  v = v1;
+}
+
+// ---- wave / block reductions (fixed order => deterministic) ---------------------------------------
+__device__ __forceinline__ double wave_sum(double x) {
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) x += __shfl_xor(x, off, kWave);
+  return x;
+}
+
+template <bool PACKED16>
+__device__ __forceinline__ uint32_t max_pattern(uint32_t a, uint32_t b) {
+  if constexpr (PACKED16) {
+    return __builtin_bit_cast(
+        uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2, a), __builtin_bit_cast(u16x2, b)));
+  } else {
+    return a > b ? a : b;
+  }
+}
+
+template <bool PACKED16>
+__device__ __forceinline__ uint32_t wave_max_pattern(uint32_t x) {
+#pragma unroll
+  for (int off = kWave / 2; off > 0; off >>= 1) {
+    x = max_pattern<PACKED16>(x, static_cast<uint32_t>(__shfl_xor(static_cast<int>(x), off, kWave)));
+  }
+  return x;
+}
+
+}  // namespace ma

@@ -1,0 +1,266 @@
+// Gradient scan: overflow flag (Sec. IV-D, Algorithm 1) fused with the sum of squares.
+//
+// One pass, HBM-bound at 2 bytes per element for 16-bit gradients.  Per lane:
+//   * flag: the running maximum of the sign-stripped bit patterns.  A pattern has an all-ones
+//     exponent exactly when, with the sign removed, it is >= the pattern of infinity
+//     (0x7F80 / 0x7C00 / 0x7F800000), so one AND and one (packed 16-bit) unsigned MAX per
+//     32-bit word replace Algorithm 1's compare-and-branch, and the single comparison happens
+//     once, in the finalize kernel.  There is no early exit: the sum needs the whole pass.
+//   * sum: each element is widened exactly to fp32, then squared and accumulated in fp64
+//     (two accumulators per lane).  fp64 keeps the result independent of gradient magnitude
+//     (no overflow of g^2 for large bf16 values, no underflow for tiny ones) and makes the
+//     clip coefficient derived from it reproducible to fp32 rounding.
+// Per block: xor-shuffle tree inside each wave, four wave results through LDS, one partial
+// per block in the caller's workspace.  A one-block finalize kernel adds the partials in index
+// order.  No floating-point atomics anywhere: the result is bit-identical from run to run.
+
+#include "ma_internal.h"
+
+namespace ma {
+
+template <int GDT>
+struct NormAcc {
+  double a0 = 0.0, a1 = 0.0;
+  uint32_t mx = 0;
+
+  __device__ __forceinline__ void word(uint32_t w) {
+    if constexpr (GDT == kF32) {
+      mx = max_pattern<false>(mx, w & 0x7FFFFFFFu);
+      const double x = static_cast<double>(bits_to_f32(w));
+      a0 = __builtin_fma(x, x, a0);
+    } else {
+      mx = max_pattern<true>(mx, w & 0x7FFF7FFFu);
+      const double lo = static_cast<double>(widen16<GDT>(w & 0xFFFFu));
+      const double hi = static_cast<double>(widen16<GDT>(w >> 16));
+      a0 = __builtin_fma(lo, lo, a0);
+      a1 = __builtin_fma(hi, hi, a1);
+    }
+  }
+  __device__ __forceinline__ void vec(u32x4 w) {
+    word(w.x);
+    word(w.y);
+    word(w.z);
+    word(w.w);
+  }
+  // one element given by index into the raw gradient buffer
+  __device__ __forceinline__ void element(MA_GLOBAL const char* g, uint64_t i) {
+    if constexpr (GDT == kF32) {
+      word(reinterpret_cast<MA_GLOBAL const uint32_t*>(g)[i]);
+    } else {
+      const uint32_t h = reinterpret_cast<MA_GLOBAL const uint16_t*>(g)[i];
+      mx = max_pattern<true>(mx, h & 0x7FFFu);
+      const double x = static_cast<double>(widen16<GDT>(h));
+      a0 = __builtin_fma(x, x, a0);
+    }
+  }
+};
+
+// One work item: kNormChunkBytes of the row's 16-byte-aligned body; item 0 also takes the
+// unaligned head elements, the last item the ragged tail.
+template <int GDT>
+__device__ __forceinline__ void norm_chunk(NormAcc<GDT>& acc, const void* g_, uint64_t n,
+                                           uint32_t head, uint64_t lc) {
+  MA_GLOBAL const char* g = to_global(static_cast<const char*>(g_));
+  constexpr uint64_t kElemBytes = (GDT == kF32) ? 4 : 2;
+  constexpr uint64_t kPerVec = 16 / kElemBytes;
+  constexpr uint64_t kChunkVecs = uint64_t(kBlock) * kNormUnroll;
+  const uint32_t tid = threadIdx.x;
+
+  if (lc == 0 && tid < head && tid < n) acc.element(g, tid);
+  if (n <= head) return;
+
+  const uint64_t body = n - head;
+  const uint64_t nvec = body / kPerVec;
+  MA_GLOBAL const u32x4* base =
+      reinterpret_cast<MA_GLOBAL const u32x4*>(g + uint64_t(head) * kElemBytes);
+  const uint64_t v0 = lc * kChunkVecs;
+
+  if (v0 + kChunkVecs <= nvec) {
+    u32x4 w[kNormUnroll];
+#pragma unroll
+    for (int u = 0; u < kNormUnroll; ++u) w[u] = ld_stream(base + v0 + tid + uint64_t(u) * kBlock);
+#pragma unroll
+    for (int u = 0; u < kNormUnroll; ++u) acc.vec(w[u]);
+  } else {
+#pragma unroll
+    for (int u = 0; u < kNormUnroll; ++u) {
+      const uint64_t vi = v0 + tid + uint64_t(u) * kBlock;
+      if (vi < nvec) acc.vec(ld_stream(base + vi));
+    }
+    // this is the row's last item: fewer than kPerVec elements remain after the last vector
+    const uint64_t t0 = uint64_t(head) + nvec * kPerVec;
+    if (t0 + tid < n) acc.element(g, t0 + tid);
+  }
+}
+
+// Block-level fold of the per-lane accumulators; thread 0 writes the block's partial.
+template <int GDT>
+__device__ __forceinline__ void norm_block_finish(NormAcc<GDT>& acc, NormPartial* partials) {
+  __shared__ double s_sum[kBlock / kWave];
+  __shared__ uint32_t s_max[kBlock / kWave];
+  const double ws = wave_sum(acc.a0 + acc.a1);
+  const uint32_t wm = wave_max_pattern<GDT != kF32>(acc.mx);
+  const int wave = threadIdx.x / kWave;
+  if ((threadIdx.x & (kWave - 1)) == 0) {
+    s_sum[wave] = ws;
+    s_max[wave] = wm;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = s_sum[0];
+    uint32_t mx = s_max[0];
+#pragma unroll
+    for (int k = 1; k < kBlock / kWave; ++k) {
+      t += s_sum[k];
+      mx = max_pattern<GDT != kF32>(mx, s_max[k]);
+    }
+    NormPartial out;
+    out.sum = t;
+    out.maxabs = mx;
+    out.pad = 0;
+    partials[blockIdx.x] = out;
+  }
+}
+
+// Flat sub-group: the row travels in the kernel arguments.
+template <int GDT>
+__global__ __launch_bounds__(kBlock) void norm_flat_kernel(Desc row, uint64_t chunks,
+                                                          NormPartial* partials) {
+  NormAcc<GDT> acc;
+  for (uint64_t c = blockIdx.x; c < chunks; c += gridDim.x) {
+    norm_chunk<GDT>(acc, row.g, row.n, row.norm_head, c);
+  }
+  norm_block_finish<GDT>(acc, partials);
+}
+
+// Largest row index in [lo, rows) whose first work item is <= c.  All operands are uniform
+// across the block, so this runs on the scalar unit.
+template <bool STEP>
+__device__ __forceinline__ uint32_t find_row(const Desc* table, uint32_t lo, uint32_t rows,
+                                             uint64_t c) {
+  uint32_t hi = rows;
+  while (hi - lo > 1) {
+    const uint32_t mid = lo + (hi - lo) / 2;
+    const uint64_t first = STEP ? table[mid].step_chunk0 : table[mid].norm_chunk0;
+    if (first <= c) {
+      lo = mid;
+    } else {
+      hi = mid;
+    }
+  }
+  return lo;
+}
+
+// Tensor list: rows live in device memory; work items are numbered across all rows.
+template <int GDT>
+__global__ __launch_bounds__(kBlock) void norm_multi_kernel(const Desc* __restrict__ table,
+                                                           uint32_t rows, uint64_t chunks,
+                                                           NormPartial* partials) {
+  NormAcc<GDT> acc;
+  uint32_t r = 0;
+  for (uint64_t c = blockIdx.x; c < chunks; c += gridDim.x) {
+    r = find_row<false>(table, r, rows, c);
+    const Desc* d = table + r;
+    norm_chunk<GDT>(acc, d->g, d->n, d->norm_head, c - d->norm_chunk0);
+  }
+  norm_block_finish<GDT>(acc, partials);
+}
+
+// Second level: one block adds `count` partials.  Thread t takes partials t, t+256, ... in
+// increasing order, then the same wave/LDS fold as above; the order is a function of `count`
+// alone.  `threshold` is the sign-stripped pattern of infinity for the gradient format.
+__global__ __launch_bounds__(kBlock) void norm_finalize_kernel(const NormPartial* __restrict__ partials,
+                                                              uint32_t count, double inv_scale_sq,
+                                                              uint32_t threshold, int packed16,
+                                                              NormResult* out) {
+  __shared__ double s_sum[kBlock / kWave];
+  __shared__ uint32_t s_max[kBlock / kWave];
+  double t = 0.0;
+  uint32_t mx = 0;
+  for (uint32_t i = threadIdx.x; i < count; i += kBlock) {
+    t += partials[i].sum;
+    const uint32_t w = partials[i].maxabs;
+    // fold the two 16-bit lanes into one value; fp32 patterns pass through
+    const uint32_t f = packed16 ? ((w & 0xFFFFu) > (w >> 16) ? (w & 0xFFFFu) : (w >> 16)) : w;
+    mx = f > mx ? f : mx;
+  }
+  t = wave_sum(t);
+  mx = wave_max_pattern<false>(mx);
+  const int wave = threadIdx.x / kWave;
+  if ((threadIdx.x & (kWave - 1)) == 0) {
+    s_sum[wave] = t;
+    s_max[wave] = mx;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double tot = s_sum[0];
+    uint32_t m = s_max[0];
+#pragma unroll
+    for (int k = 1; k < kBlock / kWave; ++k) {
+      tot += s_sum[k];
+      m = s_max[k] > m ? s_max[k] : m;
+    }
+    NormResult r;
+    r.overflow = (m >= threshold) ? 1 : 0;
+    r.reserved = 0;
+    r.sumsq = tot * inv_scale_sq;
+    *out = r;
+  }
+}
+
+// Adds scan results of several sub-groups in index order (single thread: count is tiny).
+__global__ void norm_combine_kernel(const NormResult* __restrict__ parts, uint32_t count,
+                                    NormResult* out) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  int ov = 0;
+  double s = 0.0;
+  for (uint32_t i = 0; i < count; ++i) {
+    ov |= (parts[i].overflow != 0);
+    s += parts[i].sumsq;
+  }
+  NormResult r;
+  r.overflow = ov;
+  r.reserved = 0;
+  r.sumsq = s;
+  *out = r;
+}
+
+// ---- launchers ------------------------------------------------------------------------------------
+
+static uint32_t threshold_of(int gdt) {
+  return gdt == kBF16 ? 0x7F80u : gdt == kF16 ? 0x7C00u : 0x7F800000u;
+}
+
+hipError_t launch_norm(const Desc* row_host, const Desc* table_dev, uint32_t rows, uint64_t chunks,
+                       int gdt, double inv_scale_sq, NormPartial* partials, NormResult* out,
+                       int device_cus, hipStream_t stream) {
+  uint64_t want = uint64_t(device_cus) * MA_NORM_BLOCKS_PER_CU;
+  if (want > kMaxNormBlocks) want = kMaxNormBlocks;
+  const uint32_t grid = static_cast<uint32_t>(chunks < want ? (chunks ? chunks : 1) : want);
+  if (row_host) {
+    switch (gdt) {
+      case kBF16: norm_flat_kernel<kBF16><<<grid, kBlock, 0, stream>>>(*row_host, chunks, partials); break;
+      case kF16: norm_flat_kernel<kF16><<<grid, kBlock, 0, stream>>>(*row_host, chunks, partials); break;
+      default: norm_flat_kernel<kF32><<<grid, kBlock, 0, stream>>>(*row_host, chunks, partials); break;
+    }
+  } else {
+    switch (gdt) {
+      case kBF16: norm_multi_kernel<kBF16><<<grid, kBlock, 0, stream>>>(table_dev, rows, chunks, partials); break;
+      case kF16: norm_multi_kernel<kF16><<<grid, kBlock, 0, stream>>>(table_dev, rows, chunks, partials); break;
+      default: norm_multi_kernel<kF32><<<grid, kBlock, 0, stream>>>(table_dev, rows, chunks, partials); break;
+    }
+  }
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  norm_finalize_kernel<<<1, kBlock, 0, stream>>>(partials, grid, inv_scale_sq, threshold_of(gdt),
+                                                 gdt != kF32, out);
+  return hipGetLastError();
+}
+
+hipError_t launch_norm_combine(const NormResult* parts, uint32_t count, NormResult* out,
+                               hipStream_t stream) {
+  norm_combine_kernel<<<1, kWave, 0, stream>>>(parts, count, out);
+  return hipGetLastError();
+}
+
+}  // namespace ma
