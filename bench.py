@@ -187,6 +187,8 @@ def main():
     scan_ms = sum(e[0].elapsed_time(e[1]) for e in wl.events) / len(wl.events)
     upd_ms = sum(e[1].elapsed_time(e[2]) for e in wl.events) / len(wl.events)
     launches = 4 if wl.kind == "sub" else 1      # update launches per step
+    log("update ms per step: " + " ".join("%.3f" % e[1].elapsed_time(e[2]) for e in wl.events))
+    log("scan   ms per step: " + " ".join("%.3f" % e[0].elapsed_time(e[1]) for e in wl.events))
     ov, ss = ma.read_result(wl.res)
     if ov:
         sys.exit("bench.py: unexpected overflow flag on clean synthetic gradients")

@@ -10,7 +10,10 @@
 
 namespace ma {
 
-constexpr int kBlock = 256;  // 4 waves of 64 lanes
+#ifndef MA_BLOCK
+#define MA_BLOCK 256  // threads per block (a multiple of 64)
+#endif
+constexpr int kBlock = MA_BLOCK;
 constexpr int kWave = 64;
 
 // dtype codes, numerically equal to ma_dtype in the public header
@@ -19,11 +22,21 @@ constexpr int kBF16 = 1;
 constexpr int kF16 = 2;
 constexpr int kNoLp = 3;  // update kernel variant that writes no low-precision copy
 
+// Launch shape, chosen by measurement on MI355X (256 CUs, 8 XCDs).  The update kernel moves a 1:1
+// read/write mix and is fastest with FEW resident waves that each keep a deep tile in flight (one
+// block per CU, four 4-element groups per lane, next tile prefetched): a small moving window keeps
+// DRAM pages open and read/write turnarounds rare.  The read-only scan kernel prefers more waves.
 #ifndef MA_NORM_UNROLL
-#define MA_NORM_UNROLL 4  // 16-byte loads in flight per lane in the scan kernel
+#define MA_NORM_UNROLL 8  // 16-byte loads in flight per lane in the scan kernel
 #endif
 #ifndef MA_STEP_UNROLL
-#define MA_STEP_UNROLL 2  // 4-element groups in flight per lane in the update kernel
+#define MA_STEP_UNROLL 4  // 4-element groups per lane and tile in the update kernel
+#endif
+#ifndef MA_NORM_MAP
+#define MA_NORM_MAP 0  // work-item assignment of the scan kernel (see WorkIter)
+#endif
+#ifndef MA_STEP_MAP
+#define MA_STEP_MAP 2  // work-item assignment of the update kernel (see WorkIter)
 #endif
 
 constexpr int kNormUnroll = MA_NORM_UNROLL;
@@ -82,13 +95,27 @@ template <class T>
 __device__ __forceinline__ MA_GLOBAL T* to_global(T* p) {
   return (MA_GLOBAL T*)p;
 }
+#ifndef MA_LOAD_NT
+#define MA_LOAD_NT 1  // non-temporal hint on streaming loads
+#endif
+#ifndef MA_STORE_NT
+#define MA_STORE_NT 1  // non-temporal hint on streaming stores
+#endif
 template <class T>
 __device__ __forceinline__ T ld_stream(MA_GLOBAL const T* p) {
+#if MA_LOAD_NT
   return __builtin_nontemporal_load(p);
+#else
+  return *p;
+#endif
 }
 template <class T>
 __device__ __forceinline__ void st_stream(MA_GLOBAL T* p, T x) {
+#if MA_STORE_NT
   __builtin_nontemporal_store(x, p);
+#else
+  *p = x;
+#endif
 }
 
 // ---- format conversion ----------------------------------------------------------------------
@@ -146,6 +173,36 @@ __device__ __forceinline__ void adamw_element(const StepScalars& s, float g_raw,
   m = m1;
   v = v1;
 }
+
+// ---- assignment of work items to the persistent grid ----------------------------------------------
+// MAP 0: round-robin, block b takes items b, b+G, b+2G, ...  (all blocks sweep one moving window)
+// MAP 1: one contiguous slab of items per block
+// MAP 2: XCD-contiguous: consecutive block indices are dispatched round-robin over the 8 XCDs, so
+//        block b runs on XCD b%8; each XCD owns one contiguous eighth of the items and its
+//        blocks sweep it round-robin.  Falls back to MAP 0 when the grid is not a multiple of 8.
+template <int MAP>
+struct WorkIter {
+  uint64_t c, end, stride;
+  __device__ __forceinline__ explicit WorkIter(uint64_t items) {
+    const uint64_t b = blockIdx.x, grid = gridDim.x;
+    if (MAP == 1) {
+      const uint64_t per = (items + grid - 1) / grid;
+      c = b * per;
+      end = (c + per < items) ? c + per : items;
+      stride = 1;
+    } else if (MAP == 2 && (grid & 7) == 0) {
+      const uint64_t per_xcd = (items + 7) / 8;
+      const uint64_t x = b & 7;
+      c = x * per_xcd + (b >> 3);
+      end = ((x + 1) * per_xcd < items) ? (x + 1) * per_xcd : items;
+      stride = grid >> 3;
+    } else {
+      c = b;
+      end = items;
+      stride = grid;
+    }
+  }
+};
 
 // ---- wave / block reductions (fixed order => deterministic) ---------------------------------------
 __device__ __forceinline__ double wave_sum(double x) {

@@ -6,10 +6,10 @@
 #include "ma_device.h"
 
 #ifndef MA_NORM_BLOCKS_PER_CU
-#define MA_NORM_BLOCKS_PER_CU 8  // persistent blocks per compute unit, scan kernel
+#define MA_NORM_BLOCKS_PER_CU 4  // persistent blocks per compute unit, scan kernel
 #endif
 #ifndef MA_STEP_BLOCKS_PER_CU
-#define MA_STEP_BLOCKS_PER_CU 8  // persistent blocks per compute unit, update kernel
+#define MA_STEP_BLOCKS_PER_CU 1  // persistent blocks per compute unit, update kernel
 #endif
 
 namespace ma {

@@ -127,8 +127,8 @@ template <int GDT>
 __global__ __launch_bounds__(kBlock) void norm_flat_kernel(Desc row, uint64_t chunks,
                                                           NormPartial* partials) {
   NormAcc<GDT> acc;
-  for (uint64_t c = blockIdx.x; c < chunks; c += gridDim.x) {
-    norm_chunk<GDT>(acc, row.g, row.n, row.norm_head, c);
+  for (WorkIter<MA_NORM_MAP> w(chunks); w.c < w.end; w.c += w.stride) {
+    norm_chunk<GDT>(acc, row.g, row.n, row.norm_head, w.c);
   }
   norm_block_finish<GDT>(acc, partials);
 }
@@ -158,7 +158,8 @@ __global__ __launch_bounds__(kBlock) void norm_multi_kernel(const Desc* __restri
                                                            NormPartial* partials) {
   NormAcc<GDT> acc;
   uint32_t r = 0;
-  for (uint64_t c = blockIdx.x; c < chunks; c += gridDim.x) {
+  for (WorkIter<MA_NORM_MAP> w(chunks); w.c < w.end; w.c += w.stride) {
+    const uint64_t c = w.c;
     r = find_row<false>(table, r, rows, c);
     const Desc* d = table + r;
     norm_chunk<GDT>(acc, d->g, d->n, d->norm_head, c - d->norm_chunk0);

@@ -1,0 +1,235 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+Flat configurations up to 10^8 elements are compared element by element.  The 8B-shaped list
+(8.03e9 elements), the 14B-class list as 4 streamed sub-groups (12.57e9) and a flat sub-group
+just beyond 2^31 elements are compared on samples the oracle can compute one by one -- the first
+and last 65,536 elements of every tensor, both sides of every sub-group cut, and seeded random
+blocks -- while the overflow flag and the sum of squares are checked over ALL elements.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_23254_amd import synth
+from tests._util import SUMSQ_RTOL, assert_state_close, host_f32, host_grad, oracle_hyper
+
+pytestmark = pytest.mark.gpu
+
+EDGE = 65_536
+THREADS = 16
+ma = None
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    global ma
+    from paper_2505_23254_amd import binding
+    ma = binding
+    assert torch.cuda.is_available()
+    yield
+    torch.cuda.empty_cache()
+
+
+@pytest.fixture(autouse=True)
+def _release_hbm():
+    """Hand cached blocks back between tests: the large cases need most of the device."""
+    import gc
+    gc.collect()
+    torch.cuda.empty_cache()
+    yield
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+def _need_gib(gib):
+    free, _ = torch.cuda.mem_get_info()
+    if free < gib * 2 ** 30:
+        pytest.skip("needs %.0f GiB of free HBM, device has %.0f" % (gib, free / 2 ** 30))
+
+
+def _hyper(cfg):
+    return ma.hyper(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, 1)
+
+
+def _oracle_norm_all(g: torch.Tensor, gdt: str, scale: float, piece: int = 1 << 28):
+    """Oracle flag and sum of squares over a whole device gradient, streamed through the host."""
+    ov, ss = False, 0.0
+    for a in range(0, g.numel(), piece):
+        o, s = oracle.overflow_norm(host_grad(g[a:a + piece]), gdt, scale, nthreads=THREADS)
+        ov, ss = ov or o, ss + s
+    return ov, ss
+
+
+def _merge(ranges, n):
+    out = []
+    for a, b in sorted((max(0, a), min(n, b)) for a, b in ranges):
+        if a >= b:
+            continue
+        if out and a <= out[-1][1]:
+            out[-1][1] = max(out[-1][1], b)
+        else:
+            out.append([a, b])
+    return out
+
+
+def _gather(t: torch.Tensor, ranges):
+    return torch.cat([t[a:b] for a, b in ranges])
+
+
+def _sample_state(fl, ranges, pdt):
+    return dict(p=host_f32(_gather(fl.p, ranges)), m=host_f32(_gather(fl.m, ranges)),
+                v=host_f32(_gather(fl.v, ranges)), lp=synth.bits16(_gather(fl.p_lp, ranges)), pdt=pdt)
+
+
+def _checksums(fl):
+    return [int(t.view(torch.int32 if t.element_size() == 4 else torch.int16).sum(dtype=torch.int64))
+            for t in (fl.p, fl.m, fl.v, fl.p_lp)]
+
+
+@pytest.mark.parametrize("name", ["c2", "c3a"])
+def test_flat_configs_elementwise(name):
+    cfg = synth.config(name)
+    st = synth.make_flat(cfg, device="cuda")
+    g_host = host_grad(st.g)
+    ref = dict(p=host_f32(st.p), m=host_f32(st.m), v=host_f32(st.v), lp=synth.bits16(st.p_lp), pdt="bf16")
+    ov_ref, ss_ref, c_ref = oracle.optimizer_step(ref["p"], ref["m"], ref["v"], g_host, cfg.gdt, ref["lp"],
+                                                  "bf16", oracle_hyper(cfg), cfg.step, cfg.loss_scale,
+                                                  cfg.max_norm, nthreads=THREADS)
+    assert not ov_ref and 0.05 < c_ref < 0.2          # norm ~ 10: clipping really bites
+    ws, res = ma.workspace(), ma.new_result()
+    ma.overflow_norm(st.g, cfg.loss_scale, res, ws)
+    ma.adamw_step_gated(st.p, st.m, st.v, st.g, st.p_lp, _hyper(cfg), cfg.step, cfg.loss_scale, res,
+                        cfg.max_norm)
+    ov, ss = ma.read_result(res)
+    assert not ov and abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref
+    assert np.float32(ma.clip_coef(ss, cfg.max_norm)) == c_ref
+    got = dict(p=host_f32(st.p), m=host_f32(st.m), v=host_f32(st.v), lp=synth.bits16(st.p_lp))
+    assert_state_close(got, ref, name)
+
+
+def test_fp16_overflow_variant_skips_at_full_size():
+    cfg = synth.config("c3b")
+    st = synth.make_flat(cfg, device="cuda")
+    assert len(st.inject_idx) == 17
+    assert oracle.overflow_norm(host_grad(st.g), "f16", cfg.loss_scale, nthreads=THREADS)[0] is True
+    keep = [t.clone() for t in (st.p, st.m, st.v, st.p_lp)]
+    ws, res = ma.workspace(), ma.new_result()
+    ma.overflow_norm(st.g, cfg.loss_scale, res, ws)
+    ma.adamw_step_gated(st.p, st.m, st.v, st.g, st.p_lp, _hyper(cfg), cfg.step, cfg.loss_scale, res,
+                        cfg.max_norm)
+    assert ma.read_result(res)[0] is True
+    for a, b in zip(keep, (st.p, st.m, st.v, st.p_lp)):
+        assert torch.equal(a.view(torch.int16), b.view(torch.int16))
+
+
+def _list_ranges(shapes, total, seed, n_random):
+    ranges, off = [], 0
+    for _, n in shapes:
+        ranges += [(off, off + EDGE), (off + n - EDGE, off + n)]
+        off += n
+    rng = np.random.default_rng(seed)
+    for a in rng.integers(0, total - EDGE, n_random).tolist():
+        ranges.append((a, a + EDGE))
+    return ranges
+
+
+def test_llama3_8b_list_sampled():
+    """The benchmark workload itself: 290 tensors, 8,030,257,152 elements, one scan launch and one
+    gated update launch."""
+    _need_gib(135)
+    shapes = synth.llama3_8b_shapes()
+    cfg = synth.FlatConfig("llama3_8b", 0, seed=3, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
+    ls = synth.make_list(shapes, cfg, device="cuda")
+    fl, total = ls.flat, ls.flat.p.numel()
+    assert total == 8_030_257_152                      # no padding between the views
+    ranges = _merge(_list_ranges(shapes, total, 17, 1200), total)
+    before = _sample_state(fl, ranges, "bf16")
+    g_s = host_grad(_gather(fl.g, ranges))
+    ov_ref, ss_ref = _oracle_norm_all(fl.g, "bf16", 1.0)
+    c_ref = oracle.clip_coef(ss_ref, 1.0)
+    assert not ov_ref and 0.005 < c_ref < 0.02         # norm ~ 90
+    before["lp"] = oracle.adamw_step(before["p"], before["m"], before["v"], g_s, "bf16", "bf16",
+                                     oracle_hyper(cfg), 100, 1.0, float(c_ref), nthreads=THREADS)
+    plan = ma.MultiPlan(ls.p, ls.m, ls.v, ls.g, ls.p_lp)
+    ws, res = ma.workspace(), ma.new_result()
+    ma.multi_overflow_norm(plan, 1.0, res, ws)
+    ma.multi_adamw_step_gated(plan, _hyper(cfg), 100, 1.0, res, 1.0)
+    ov, ss = ma.read_result(res)
+    assert not ov and abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref
+    assert np.float32(ma.clip_coef(ss, 1.0)) == c_ref
+    assert_state_close(_sample_state(fl, ranges, "bf16"), before, "8B list sample")
+    # one NaN in a norm vector: the whole list is skipped, checked over every byte via checksums
+    sums = _checksums(fl)
+    ls.g[8].view(torch.int16)[4095] = 0x7FC0
+    ma.multi_overflow_norm(plan, 1.0, res, ws)
+    ma.multi_adamw_step_gated(plan, _hyper(cfg), 101, 1.0, res, 1.0)
+    assert ma.read_result(res)[0] is True
+    assert _checksums(fl) == sums
+
+
+def test_14b_class_four_sub_groups_sampled():
+    """12,567,592,960 elements as 4 equal flat sub-groups (3,141,898,240 each, beyond 2^31) cut
+    without regard to tensor boundaries: 4 scans, 1 combine, 4 gated updates on one stream."""
+    _need_gib(210)
+    shapes = synth.qwen14b_class_shapes()
+    total = sum(n for _, n in shapes)
+    cfg = synth.FlatConfig("qwen14b_4sub", 0, seed=4, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
+    fl = synth.make_flat(cfg, device="cuda", n=total)
+    sub = total // 4
+    assert sub == 3_141_898_240
+    ranges = _list_ranges(shapes, total, 19, 600)
+    for k in range(1, 4):
+        ranges.append((k * sub - EDGE, k * sub + EDGE))
+    ranges = _merge(ranges, total)
+    before = _sample_state(fl, ranges, "bf16")
+    g_s = host_grad(_gather(fl.g, ranges))
+    ss_ref = 0.0
+    for k in range(4):
+        ov_k, ss_k = _oracle_norm_all(fl.g[k * sub:(k + 1) * sub], "bf16", 1.0)
+        assert not ov_k
+        ss_ref += ss_k
+    c_ref = oracle.clip_coef(ss_ref, 1.0)
+    before["lp"] = oracle.adamw_step(before["p"], before["m"], before["v"], g_s, "bf16", "bf16",
+                                     oracle_hyper(cfg), 100, 1.0, float(c_ref), nthreads=THREADS)
+    ws, parts, res = ma.workspace(), ma.new_result(4), ma.new_result()
+    for k in range(4):
+        ma.overflow_norm(fl.g[k * sub:(k + 1) * sub], 1.0, parts, ws, index=k)
+    ma.norm_combine(parts, 4, res)
+    for k in range(4):
+        s = slice(k * sub, (k + 1) * sub)
+        ma.adamw_step_gated(fl.p[s], fl.m[s], fl.v[s], fl.g[s], fl.p_lp[s], _hyper(cfg), 100, 1.0, res, 1.0)
+    ov, ss = ma.read_result(res)
+    assert not ov and abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref
+    assert np.float32(ma.clip_coef(ss, 1.0)) == c_ref
+    assert_state_close(_sample_state(fl, ranges, "bf16"), before, "14B sub-groups sample")
+
+
+def test_flat_sub_group_beyond_2_to_31():
+    """n = 2^31 + 5: 64-bit indexing, ragged tail of one element group plus one."""
+    _need_gib(40)
+    n = (1 << 31) + 5
+    cfg = synth.FlatConfig("big", n, seed=6, m_std=1e-4, v_std=1e-8, step=9, gdt="f16", loss_scale=512.0,
+                           max_norm=2.0)
+    fl = synth.make_flat(cfg, device="cuda")
+    rng = np.random.default_rng(23)
+    ranges = [(0, EDGE), (n - EDGE, n), ((1 << 31) - EDGE, (1 << 31) + 5), ((1 << 30) - 999, (1 << 30) + 999)]
+    ranges += [(a, a + 4099) for a in rng.integers(0, n - 5000, 300).tolist()]
+    ranges = _merge(ranges, n)
+    before = _sample_state(fl, ranges, "bf16")
+    g_s = host_grad(_gather(fl.g, ranges))
+    ov_ref, ss_ref = _oracle_norm_all(fl.g, "f16", 512.0)
+    c_ref = oracle.clip_coef(ss_ref, 2.0)
+    assert not ov_ref and c_ref < 1
+    before["lp"] = oracle.adamw_step(before["p"], before["m"], before["v"], g_s, "f16", "bf16",
+                                     oracle_hyper(cfg), 9, 512.0, float(c_ref), nthreads=THREADS)
+    ws, res = ma.workspace(), ma.new_result(2)
+    ma.overflow_norm(fl.g, 512.0, res, ws)
+    ma.adamw_step_gated(fl.p, fl.m, fl.v, fl.g, fl.p_lp, _hyper(cfg), 9, 512.0, res, 2.0)
+    ov, ss = ma.read_result(res)
+    assert not ov and abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref
+    assert_state_close(_sample_state(fl, ranges, "bf16"), before, "2^31+5")
+    # an inf in the very last element is seen
+    fl.g.view(torch.int16)[n - 1] = 0x7C00
+    ma.overflow_norm(fl.g, 512.0, res, ws, index=1)
+    assert ma.read_result(res, 1)[0] is True
