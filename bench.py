@@ -33,6 +33,32 @@ STEP_BYTES_PER_PARAM = 28.0    # update kernel: read p,m,v (12) + g (2), write p
 SCAN_BYTES_PER_PARAM = 2.0     # scan kernel: read g
 
 
+# HBM bytes per launch of the update kernel from hardware counters (rocprofv3 --pmc FETCH_SIZE /
+# WRITE_SIZE, scaled by a plain copy of known size; summary in
+# profiles/hbm_traffic_counters__llama3_8b.txt).  Valid only for the kernel sources they were taken
+# with: when the digest of csrc/ differs, the figure is reported as null.
+MEASURED_TRAFFIC = {
+    "csrc_sha256": "87525c643d6b34d58ecbc6cf3e7ddbaa4f62a98b7adbac72b605cab40a19a53b",
+    "llama3_8b": 224856038917,
+}
+
+
+def csrc_digest():
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2505_23254_amd", "csrc", "*"))):
+        with open(f, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()
+
+
+def measured_traffic(workload):
+    if workload in MEASURED_TRAFFIC and csrc_digest() == MEASURED_TRAFFIC["csrc_sha256"]:
+        return MEASURED_TRAFFIC[workload]
+    return None
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -159,6 +185,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 28)
     ap.add_argument("--cpu-passes", type=int, default=4)
+    ap.add_argument("--copy-calibration", type=int, default=0, metavar="BYTES",
+                    help="after the timed region, run one plain device copy of BYTES bytes (reads "
+                         "BYTES, writes BYTES): the known-size reference for hardware byte counters")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU's share of the optimizer step; "
@@ -184,6 +213,14 @@ def main():
     t1 = time.perf_counter()
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
+    if args.copy_calibration > 0:
+        src = torch.ones(args.copy_calibration, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        log("copy calibration: %d bytes read, %d bytes written" % (src.numel(), dst.numel()))
+        del src, dst
     scan_ms = sum(e[0].elapsed_time(e[1]) for e in wl.events) / len(wl.events)
     upd_ms = sum(e[1].elapsed_time(e[2]) for e in wl.events) / len(wl.events)
     launches = 4 if wl.kind == "sub" else 1      # update launches per step
@@ -208,7 +245,8 @@ def main():
         "roofline": {
             "bound": "hbm", "kernel": "AdamW update (+ low-precision copy)",
             "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+            "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
+            "algorithmic_bytes_per_launch": STEP_BYTES_PER_PARAM * wl.n / launches,
             "bytes_per_param": STEP_BYTES_PER_PARAM, "params_per_launch": wl.n / launches,
             "avg_launch_ms": upd_ms / launches,
             "scan": {"avg_ms": scan_ms, "bytes_per_param": SCAN_BYTES_PER_PARAM,

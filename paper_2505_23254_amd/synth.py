@@ -70,6 +70,7 @@ class FlatState:
     g: torch.Tensor           # low-precision gradient, already multiplied by loss_scale
     p_lp: torch.Tensor
     inject_idx: List[int] = field(default_factory=list)
+    arena: Optional[torch.Tensor] = None      # the allocation the five views are cut from
 
 
 def _fill_normal(buf: torch.Tensor, std: float, gen: torch.Generator, piece: int = 1 << 27):
@@ -111,24 +112,47 @@ def plant_nonfinite(g: torch.Tensor, gdt: str, count: int, seed: int) -> List[in
     return idx
 
 
+ARENA_ALIGN = 2 << 20   # every buffer of a state starts on a 2 MiB boundary of the arena
+
+
+def carve_state(n: int, gdt: str, pdt: str, device: str):
+    """One allocation for a whole optimizer state, cut into p | m | v | g | p_lp in that order.
+
+    A single arena keeps the five streams of the update kernel at fixed, known distances from
+    each other (the kernel's speed depends on where the streams lie relative to each other in
+    HBM, and one allocation makes that reproducible from process to process).
+    """
+    sizes = [4 * n, 4 * n, 4 * n, 2 * n, 2 * n]
+    offs, total = [], 0
+    for sz in sizes:
+        offs.append(total)
+        total += (sz + ARENA_ALIGN - 1) // ARENA_ALIGN * ARENA_ALIGN
+    arena = torch.empty(max(total, 1), dtype=torch.uint8, device=device)
+    dts = [torch.float32, torch.float32, torch.float32, _TORCH_LP[gdt], _TORCH_LP[pdt]]
+    views = [arena[o:o + sz].view(dt) for o, sz, dt in zip(offs, sizes, dts)]
+    return arena, views
+
+
 def make_flat(cfg: FlatConfig, device: str = "cpu", n: Optional[int] = None) -> FlatState:
     """Allocate and fill one flat sub-group on `device` (n overrides cfg.n for small cases)."""
     n = cfg.n if n is None else n
     gen = torch.Generator(device=device)
     gen.manual_seed(cfg.seed)
-    p = torch.empty(n, dtype=torch.float32, device=device)
+    arena, (p, m, v, g, p_lp) = carve_state(n, cfg.gdt, cfg.pdt, device)
     _fill_normal(p, cfg.p_std, gen)
-    m = torch.zeros(n, dtype=torch.float32, device=device)
+    m.zero_()
     if cfg.m_std > 0:
         _fill_normal(m, cfg.m_std, gen)
-    v = torch.zeros(n, dtype=torch.float32, device=device)
+    v.zero_()
     if cfg.v_std > 0:
         _fill_normal(v, cfg.v_std, gen)
         v.abs_()
-    g = torch.empty(n, dtype=_TORCH_LP[cfg.gdt], device=device)
     _fill_grad(g, cfg.g_std, cfg.loss_scale, gen)
-    p_lp = p.to(_TORCH_LP[cfg.pdt])
+    piece = 1 << 27
+    for a in range(0, n, piece):
+        p_lp[a:a + piece].copy_(p[a:a + piece])       # library cast: the copy starts in sync with p
     st = FlatState(p, m, v, g, p_lp)
+    st.arena = arena
     if cfg.n_inject > 0 and n > 0:
         st.inject_idx = plant_nonfinite(g, cfg.gdt, min(cfg.n_inject, n), cfg.seed)
     return st
