@@ -36,25 +36,27 @@ SCAN_BYTES_PER_PARAM = 2.0     # scan kernel: read g
 # HBM bytes per launch of the update kernel from hardware counters (rocprofv3 --pmc FETCH_SIZE /
 # WRITE_SIZE, scaled by a plain copy of known size; summary in
 # profiles/hbm_traffic_counters__llama3_8b.txt).  Valid only for the kernel sources they were taken
-# with: when the digest of csrc/ differs, the figure is reported as null.
+# with: when the digest of the kernel sources differs, the figure is reported as null.
 MEASURED_TRAFFIC = {
-    "csrc_sha256": "87525c643d6b34d58ecbc6cf3e7ddbaa4f62a98b7adbac72b605cab40a19a53b",
+    "kernel_sha256": "22437e4c5da565b6384aab671dba479c24ec9f764bb4fcc0eae7fdd4dbf7577f",
     "llama3_8b": 224856038917,
 }
 
 
-def csrc_digest():
-    import glob
+KERNEL_SOURCES = ("ma_device.h", "ma_internal.h", "ma_norm.hip", "ma_adamw.hip")
+
+
+def kernel_digest():
     import hashlib
     h = hashlib.sha256()
-    for f in sorted(glob.glob(os.path.join(ROOT, "paper_2505_23254_amd", "csrc", "*"))):
-        with open(f, "rb") as fh:
+    for f in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2505_23254_amd", "csrc", f), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()
 
 
 def measured_traffic(workload):
-    if workload in MEASURED_TRAFFIC and csrc_digest() == MEASURED_TRAFFIC["csrc_sha256"]:
+    if workload in MEASURED_TRAFFIC and kernel_digest() == MEASURED_TRAFFIC["kernel_sha256"]:
         return MEASURED_TRAFFIC[workload]
     return None
 

@@ -84,7 +84,7 @@ typedef struct ma_tensor {
 /* Host-side handle of a prepared tensor list (plain data, caller-owned, copyable). */
 typedef struct ma_multi_plan {
   const void* table_dev; /* device table written by ma_multi_prepare */
-  uint64_t entries;      /* table rows (a misaligned tensor may take two) */
+  uint64_t entries;      /* table rows (one per non-empty tensor) */
   uint64_t total_elems;
   uint64_t norm_chunks;  /* work items of the scan kernel */
   uint64_t step_chunks;  /* work items of the update kernel */
@@ -111,6 +111,24 @@ size_t ma_workspace_bytes(void);
  *   c = min(1, max_norm / (sqrt(sumsq) + 1e-6)),  evaluated in fp64, rounded once to fp32;
  * max_norm <= 0 disables clipping (c = 1). */
 float ma_clip_coef(double sumsq, float max_norm);
+
+/* Host helper: the nine fp32 scalars one AdamW step uses, in the order
+ *   {beta1, beta2, 1-beta1, 1-beta2, eps, lr/(1-beta1^step), 1/sqrt(1-beta2^step), lr*wd,
+ *    clip_coef/loss_scale},
+ * each evaluated in fp64 from the fp32 arguments and rounded once (the update kernels receive
+ * exactly these).  Same argument checks as ma_adamw_step. */
+int ma_step_scalars(const ma_hyper* hyper, int64_t step, float loss_scale, float clip_coef,
+                    float out_host[9]);
+
+/* Host helper: how the library splits one tensor into work items, from its pointers alone
+ * (nothing is dereferenced).  norm_items / step_items: work items of the scan / update kernel;
+ * norm_head: elements before the gradient's first 16-byte boundary (scalar path);
+ * step_head: elements before the first 4-element group common to all buffers;
+ * step_vec: 1 if the 128-bit update path applies after step_head elements, 0 if the buffers'
+ * alignments disagree and the scalar path is used.  Any out pointer may be NULL. */
+int ma_plan_tensor(const ma_tensor* tensor_host, ma_dtype gdt, uint64_t* norm_items,
+                   uint64_t* step_items, uint32_t* norm_head, uint32_t* step_head,
+                   uint32_t* step_vec);
 
 /* ---- step 1: overflow scan fused with the sum of squares ---------------------------------- */
 

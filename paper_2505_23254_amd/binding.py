@@ -57,6 +57,8 @@ def _load() -> ctypes.CDLL:
         "ma_last_error": ([], ctypes.c_char_p),
         "ma_workspace_bytes": ([], sz),
         "ma_clip_coef": ([f64, f32], f32),
+        "ma_step_scalars": ([vp, i64, f32, f32, vp], ctypes.c_int),
+        "ma_plan_tensor": ([vp, i32, vp, vp, vp, vp, vp], ctypes.c_int),
         "ma_overflow_norm": ([vp, i32, sz, f32, vp, vp, sz, vp], ctypes.c_int),
         "ma_norm_combine": ([vp, sz, vp, vp], ctypes.c_int),
         "ma_adamw_step": ([vp, vp, vp, vp, i32, vp, i32, sz, vp, i64, f32, f32, vp], ctypes.c_int),
@@ -109,6 +111,23 @@ def version() -> int:
 
 def clip_coef(sumsq: float, max_norm: float) -> float:
     return lib.ma_clip_coef(float(sumsq), float(max_norm))
+
+
+def step_scalars(h: Hyper, step: int, loss_scale: float = 1.0, clip: float = 1.0):
+    """The nine fp32 scalars of one step (ma_step_scalars), as a list of Python floats."""
+    out = (ctypes.c_float * 9)()
+    _check(lib.ma_step_scalars(ctypes.byref(h), int(step), loss_scale, clip, out))
+    return list(out)
+
+
+def plan_tensor(p, m, v, g, lp, n: int, gdt: int):
+    """ma_plan_tensor on raw addresses: (norm_items, step_items, norm_head, step_head, step_vec)."""
+    t = Tensor(p, m, v, g, lp, n)
+    ni, si = ctypes.c_uint64(), ctypes.c_uint64()
+    nh, sh, sv = ctypes.c_uint32(), ctypes.c_uint32(), ctypes.c_uint32()
+    _check(lib.ma_plan_tensor(ctypes.byref(t), gdt, ctypes.byref(ni), ctypes.byref(si),
+                              ctypes.byref(nh), ctypes.byref(sh), ctypes.byref(sv)))
+    return ni.value, si.value, nh.value, sh.value, sv.value
 
 
 def workspace(device="cuda") -> torch.Tensor:

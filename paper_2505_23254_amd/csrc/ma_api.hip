@@ -205,6 +205,43 @@ float ma_clip_coef(double sumsq, float max_norm) {
   return float(c < 1.0 ? c : 1.0);
 }
 
+int ma_step_scalars(const ma_hyper* hyper, int64_t step, float loss_scale, float clip_coef,
+                    float out_host[9]) {
+  if (int rc = check_hyper(hyper, step)) return rc;
+  if (int rc = check_scale(loss_scale)) return rc;
+  if (!(clip_coef > 0.0f && clip_coef <= 1.0f))
+    return fail(MA_ERR_ARG, "clip_coef must be in (0, 1] (got %g)", double(clip_coef));
+  if (!out_host) return fail(MA_ERR_NULL, "out_host is NULL");
+  const ma::StepScalars s = host_scalars(*hyper, step, loss_scale, clip_coef);
+  const float a[9] = {s.beta1, s.beta2, s.omb1, s.omb2, s.eps,
+                      s.step_size, s.inv_sqrt_bc2, s.decay, s.gscale};
+  std::memcpy(out_host, a, sizeof(a));
+  return MA_OK;
+}
+
+int ma_plan_tensor(const ma_tensor* t, ma_dtype gdt, uint64_t* norm_items, uint64_t* step_items,
+                   uint32_t* norm_head, uint32_t* step_head, uint32_t* step_vec) {
+  if (!t) return fail(MA_ERR_NULL, "tensor_host is NULL");
+  if (!dtype_ok(gdt)) return fail(MA_ERR_DTYPE, "unsupported gradient dtype %d", int(gdt));
+  ma::Desc d{};
+  d.p = t->p32;
+  d.m = t->m;
+  d.v = t->v;
+  d.g = t->grad;
+  d.lp = t->p_lp;
+  d.n = t->n;
+  uint64_t nc = 0, sc = 0;
+  if (t->n > 0) {
+    if (int rc = plan_row(d, gdt, t->p_lp != nullptr, &nc, &sc)) return rc;
+  }
+  if (norm_items) *norm_items = nc;
+  if (step_items) *step_items = sc;
+  if (norm_head) *norm_head = d.norm_head;
+  if (step_head) *step_head = d.step_head;
+  if (step_vec) *step_vec = d.step_vec;
+  return MA_OK;
+}
+
 int ma_overflow_norm(const void* grad, ma_dtype gdt, size_t n, float loss_scale,
                      ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream) {
   if (!dtype_ok(gdt)) return fail(MA_ERR_DTYPE, "unsupported gradient dtype %d", int(gdt));

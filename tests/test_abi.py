@@ -106,3 +106,50 @@ def test_multi_argument_errors():
     assert ma.lib.ma_multi_adamw_step(ctypes.byref(plan), ctypes.byref(H), 1, 1.0, 1.0, None) == ma.MA_ERR_ARG
     assert ma.lib.ma_multi_overflow_norm(ctypes.byref(plan), 1.0, A, A, 1 << 20, None) == ma.MA_ERR_ARG
     assert ma.lib.ma_multi_adamw_step_gated(None, ctypes.byref(H), 1, 1.0, A, 1.0, None) == ma.MA_ERR_NULL
+
+
+def test_host_step_scalars_match_oracle_bit_for_bit():
+    import itertools
+    for lr, b1, b2, eps, wd, bc in itertools.product((1e-5, 3e-2, 0.0), (0.9, 0.0, 0.8), (0.999, 0.95),
+                                                     (1e-8, 1e-3), (0.01, 0.0), (1, 0)):
+        for step, scale, clip in ((1, 1.0, 1.0), (100, 65536.0, 0.37), (10 ** 6, 3.0, 1e-3), (7, 0.5, 1.0)):
+            got = np.array(ma.step_scalars(ma.hyper(lr, b1, b2, eps, wd, bc), step, scale, clip), np.float32)
+            ref = oracle.step_scalars(oracle.hyper(lr, b1, b2, eps, wd, bc), step, scale, clip)
+            assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), (lr, b1, b2, eps, wd, bc, step)
+
+
+def _model_plan(p, m, v, g, lp, n, gbytes, norm_chunk_bytes, step_chunk_elems):
+    """Independent model of the work split, from the contract in the header."""
+    norm_head = ((16 - g % 16) % 16) // gbytes
+    norm_items = 1 if n <= norm_head else -(-(n - norm_head) // (norm_chunk_bytes // gbytes))
+    h = ((16 - p % 16) % 16) // 4
+    ok = all((a + h * eb) % (4 * eb) == 0 for a, eb in ((m, 4), (v, 4), (g, gbytes)) + (((lp, 2),) if lp else ()))
+    if ok:
+        step_items = 1 if n <= h else -(-(n - h) // step_chunk_elems)
+        return norm_items, step_items, norm_head, h, 1
+    return norm_items, -(-n // step_chunk_elems), norm_head, 0, 0
+
+
+def test_work_split_of_a_tensor():
+    # the two work-item sizes are read off two calls, then every alignment class is checked
+    base = 0x7F0000000000
+    big = 1 << 40
+    ni, si, *_ = ma.plan_tensor(base, base, base, base, base, big, ma.MA_BF16)
+    norm_chunk_bytes, step_chunk_elems = 2 * big // ni, big // si
+    assert norm_chunk_bytes % (256 * 16) == 0 and step_chunk_elems % 1024 == 0
+    rng = np.random.default_rng(3)
+    for gdt, gb in ((ma.MA_BF16, 2), (ma.MA_F16, 2), (ma.MA_F32, 4)):
+        for trial in range(400):
+            k = int(rng.integers(0, 8))
+            same = trial % 2 == 0
+            offs = [k] * 5 if same else [int(x) for x in rng.integers(0, 8, 5)]
+            p, m, v = (base + 4 * o for o in offs[:3])
+            g = base + gb * offs[3]
+            lp = (base + 2 * offs[4]) if trial % 5 else None
+            n = int(rng.choice([1, 2, 3, 4, 5, 7, 8, 9, 4095, 4096, 4097, 16384, 16385, 100003, 2 ** 31 + 5]))
+            got = ma.plan_tensor(p, m, v, g, lp, n, gdt)
+            want = _model_plan(p, m, v, g, lp or 0, n, gb, norm_chunk_bytes, step_chunk_elems)
+            assert got == want, (offs, n, gdt, got, want)
+            if same:
+                assert got[4] == 1 and got[3] == (4 - k % 4) % 4
+    assert ma.plan_tensor(base, base, base, base, base, 0, ma.MA_BF16) == (0, 0, 0, 0, 0)
