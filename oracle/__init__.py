@@ -43,7 +43,28 @@ def _load():
     lib.ora_optimizer_step.argtypes = [vp, vp, vp, vp, i32, vp, i32, sz, vp, i64, f32, f32, i32,
                                        vp, vp]
     lib.ora_optimizer_step.restype = i32
+    lib.ora_grad_accumulate.argtypes = [vp, vp, i32, sz, i32]
+    lib.ora_grad_accumulate.restype = None
+    lib.ora_truncate_bf16.argtypes = [vp, vp, sz]
+    lib.ora_truncate_bf16.restype = None
+    lib.ora_adamw_step_bf16.argtypes = [vp, vp, vp, vp, i32, sz, vp, i64, f32, f32, i32]
+    lib.ora_adamw_step_bf16.restype = None
+    lib.ora_scaler_update.argtypes = [vp, vp, i32]
+    lib.ora_scaler_update.restype = None
+    lib.ora_optimizer_step_auto.argtypes = [vp, vp, vp, vp, i32, vp, i32, sz, vp, vp, vp, f32, i32, vp]
+    lib.ora_optimizer_step_auto.restype = i32
     return lib
+
+
+class ScalerCfg(ctypes.Structure):
+    _fields_ = [("backoff", ctypes.c_float), ("growth", ctypes.c_float),
+                ("min_scale", ctypes.c_float), ("max_scale", ctypes.c_float),
+                ("window", ctypes.c_int32)]
+
+
+class ScalerState(ctypes.Structure):
+    _fields_ = [("scale", ctypes.c_float), ("good_steps", ctypes.c_int32),
+                ("step", ctypes.c_int64), ("skipped", ctypes.c_int64)]
 
 
 _lib = _load()
@@ -153,3 +174,55 @@ def optimizer_step(p, m, v, grad, gdt, p_lp, pdt, h, step, loss_scale=1.0, max_n
                                  _DT[pdt], p.size, ctypes.byref(h), int(step), loss_scale,
                                  float(max_norm), nthreads, ctypes.byref(ss), ctypes.byref(c))
     return bool(ov), ss.value, np.float32(c.value)
+
+
+def grad_accumulate(acc, grad, gdt, first):
+    """acc (fp32, in place) = grad if first else acc + grad, one fp32 addition per element."""
+    _chk(acc, np.float32, "acc")
+    _chk(grad, _grad_dtype(gdt), "grad")
+    if acc.size != grad.size:
+        raise ValueError("size mismatch")
+    _lib.ora_grad_accumulate(_ptr(acc), _ptr(grad), _DT[gdt], acc.size, int(bool(first)))
+
+
+def truncate_bf16(x):
+    _chk(x, np.float32, "x")
+    out = np.empty(x.shape, np.uint16)
+    _lib.ora_truncate_bf16(_ptr(x), _ptr(out), x.size)
+    return out
+
+
+def adamw_step_bf16(p, m, v, grad, gdt, h, step, loss_scale=1.0, clip=1.0, nthreads=1):
+    """AdamW with p, m, v held as bf16 bit patterns (uint16, in place), truncating stores."""
+    for a, nm in ((p, "p"), (m, "m"), (v, "v")):
+        _chk(a, np.uint16, nm)
+    _chk(grad, _grad_dtype(gdt), "grad")
+    if not (p.size == m.size == v.size == grad.size):
+        raise ValueError("size mismatch")
+    _lib.ora_adamw_step_bf16(_ptr(p), _ptr(m), _ptr(v), _ptr(grad), _DT[gdt], p.size,
+                             ctypes.byref(h), int(step), loss_scale, float(clip), nthreads)
+
+
+def scaler_cfg(backoff=0.5, growth=2.0, min_scale=1.0, max_scale=2.0 ** 24, window=1000):
+    return ScalerCfg(backoff, growth, min_scale, max_scale, window)
+
+
+def scaler_state(scale=65536.0, good_steps=0, step=0, skipped=0):
+    return ScalerState(scale, good_steps, step, skipped)
+
+
+def scaler_update(state, cfg, overflow):
+    _lib.ora_scaler_update(ctypes.byref(state), ctypes.byref(cfg), int(bool(overflow)))
+
+
+def optimizer_step_auto(p, m, v, grad, gdt, p_lp, pdt, h, state, cfg, max_norm=0.0, nthreads=1):
+    """One iteration driven by the scaler state.  Returns (overflow, sumsq)."""
+    for a, nm in ((p, "p"), (m, "m"), (v, "v")):
+        _chk(a, np.float32, nm)
+    _chk(grad, _grad_dtype(gdt), "grad")
+    _chk(p_lp, np.uint16, "p_lp")
+    ss = ctypes.c_double(0.0)
+    ov = _lib.ora_optimizer_step_auto(_ptr(p), _ptr(m), _ptr(v), _ptr(grad), _DT[gdt], _ptr(p_lp),
+                                      _DT[pdt], p.size, ctypes.byref(h), ctypes.byref(state),
+                                      ctypes.byref(cfg), float(max_norm), nthreads, ctypes.byref(ss))
+    return bool(ov), ss.value

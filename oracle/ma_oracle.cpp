@@ -23,11 +23,17 @@
 //     definition (nearest representable value, ties to the even significand).
 //   * Sum of squares / clipping -- not in the paper; global-L2-norm clipping as commonly
 //     paired with this step.  sumsq = sum_i (g_i / S)^2 in fp64, index order.
+//   * Gradient accumulation into the fp32 flat buffer -- Sec. III-C.
+//   * bf16 optimizer states stored by truncation -- Extended Experiments.
+//   * Dynamic loss scale -- Sec. III-C gives the reaction to an overflow, not a policy; the
+//     policy below is a stated reading.
 //
 // Parity pins (tests/test_oracle_*.py): casts vs. two independent library converters and
 // hand-worked ties; flag vs. the exponent-mask rule of Algorithm 1 on every 16-bit pattern;
 // sumsq vs. closed forms and exact rational arithmetic; AdamW vs. the first-step closed form,
-// an fp64 evaluation of the textbook formula, and a library AdamW run in fp64.
+// an fp64 evaluation of the textbook formula, and a library AdamW run in fp64; accumulation vs.
+// IEEE fp32 addition in a library; the bf16-state step vs. widen / fp32 step / shift; the loss
+// scale vs. hand-worked sequences (tests/golden/loss_scale_sequence.txt).
 //
 // Build: g++ -O2 -ffp-contract=off -std=c++17 -shared -fPIC (see oracle/build.py).
 // -ffp-contract=off matters: every fp32 operation below rounds once, and additions happen
@@ -381,6 +387,108 @@ int32_t ora_optimizer_step(float* p, float* m, float* v, const void* grad, int g
   if (clip_out) *clip_out = c;
   ora_adamw_step(p, m, v, grad, gdt, p_lp, pdt, n, hyper, step, loss_scale, c, nthreads);
   return 0;
+}
+
+// ---- gradient accumulation into the fp32 flat buffer ------------------------------------------
+// Sec. III-C: the partition's flat gradient buffer is kept in fp32 so that low-precision
+// micro-batch gradients can be accumulated into it.  One fp32 addition per element; the first
+// micro-batch of an iteration overwrites (first != 0), later ones add.
+void ora_grad_accumulate(float* acc, const void* grad, int gdt, size_t n, int first) {
+  for (size_t i = 0; i < n; ++i) {
+    const float g = widen(grad, gdt, i);
+    acc[i] = first ? g : acc[i] + g;
+  }
+}
+
+// ---- half-precision optimizer states -----------------------------------------------------------
+// Extended Experiments (bf16 half-precision optimizer): parameters, gradients and both moments
+// are held in bf16; the only conversion back from fp32 is a direct truncation (the low 16 bits
+// are dropped).  The arithmetic between widening and truncation is the fp32 step above.
+// Reading of a silent point: a NaN whose payload lies only in the dropped bits would truncate to
+// infinity; it is kept a NaN by setting the quiet bit.
+uint16_t ora_truncate_bf16_one(float x) {
+  const uint32_t b = bits_of(x);
+  uint16_t h = static_cast<uint16_t>(b >> 16);
+  if (std::isnan(x)) h |= 0x0040;
+  return h;
+}
+
+void ora_truncate_bf16(const float* in, uint16_t* out, size_t n) {
+  for (size_t i = 0; i < n; ++i) out[i] = ora_truncate_bf16_one(in[i]);
+}
+
+void ora_adamw_step_bf16(uint16_t* p, uint16_t* m, uint16_t* v, const void* grad, int gdt, size_t n,
+                         const void* hyper, int64_t step, float loss_scale, float clip_coef,
+                         int nthreads) {
+  Hyper h;
+  std::memcpy(&h, hyper, sizeof(Hyper));
+  const StepScalars s = make_scalars(h, step, loss_scale, clip_coef);
+  auto range = [&](size_t lo, size_t hi, int) {
+    for (size_t i = lo; i < hi; ++i) {
+      float pf = widen_bf16(p[i]), mf = widen_bf16(m[i]), vf = widen_bf16(v[i]);
+      adamw_element(s, widen(grad, gdt, i), pf, mf, vf);
+      p[i] = ora_truncate_bf16_one(pf);
+      m[i] = ora_truncate_bf16_one(mf);
+      v[i] = ora_truncate_bf16_one(vf);
+    }
+  };
+  if (nthreads <= 1) {
+    range(0, n, 0);
+  } else {
+    over_ranges(n, nthreads, range);
+  }
+}
+
+// ---- dynamic loss scale --------------------------------------------------------------------------
+// Sec. III-C: when any value overflows, the scale factor is reduced (and the step is skipped).
+// The paper gives no policy; the reading is the usual dynamic scaling: on overflow multiply the
+// scale by `backoff` (not below min_scale) and restart the count of clean steps; after `window`
+// clean steps in a row multiply it by `growth` (not above max_scale).  `step` counts applied
+// updates; a skipped iteration does not advance it.
+struct ScalerCfg {
+  float backoff, growth, min_scale, max_scale;
+  int32_t window;
+};
+struct ScalerState {
+  float scale;
+  int32_t good_steps;
+  int64_t step;
+  int64_t skipped;
+};
+
+void ora_scaler_update(void* state, const void* cfg_, int32_t overflow) {
+  ScalerState st;
+  ScalerCfg cfg;
+  std::memcpy(&st, state, sizeof(st));
+  std::memcpy(&cfg, cfg_, sizeof(cfg));
+  if (overflow) {
+    const float s = st.scale * cfg.backoff;
+    st.scale = s < cfg.min_scale ? cfg.min_scale : s;
+    st.good_steps = 0;
+    st.skipped += 1;
+  } else {
+    st.step += 1;
+    st.good_steps += 1;
+    if (st.good_steps >= cfg.window) {
+      const float s = st.scale * cfg.growth;
+      st.scale = s > cfg.max_scale ? cfg.max_scale : s;
+      st.good_steps = 0;
+    }
+  }
+  std::memcpy(state, &st, sizeof(st));
+}
+
+// One whole iteration driven by the scaler state: scan at the current scale; on overflow skip and
+// back off; otherwise clip, apply update number step+1, and count the clean step.
+int32_t ora_optimizer_step_auto(float* p, float* m, float* v, const void* grad, int gdt, void* p_lp,
+                                int pdt, size_t n, const void* hyper, void* state, const void* cfg,
+                                float max_norm, int nthreads, double* sumsq_out) {
+  ScalerState st;
+  std::memcpy(&st, state, sizeof(st));
+  const int32_t ov = ora_optimizer_step(p, m, v, grad, gdt, p_lp, pdt, n, hyper, st.step + 1, st.scale,
+                                        max_norm, nthreads, sumsq_out, nullptr);
+  ora_scaler_update(state, cfg, ov);
+  return ov;
 }
 
 }  // extern "C"
