@@ -94,6 +94,25 @@ typedef struct ma_multi_plan {
   uint32_t reserved;
 } ma_multi_plan;
 
+/* Dynamic loss-scale state, 24 bytes, lives in device memory (Sec. III-C: when a value overflows,
+ * the scale factor is reduced and the step skipped).  Written by ma_scaler_init / ma_scaler_update,
+ * read on the device by the *_auto entry points. */
+typedef struct ma_scaler_state {
+  float scale;        /* current loss scale */
+  int32_t good_steps; /* clean steps since the scale last changed */
+  int64_t step;       /* updates applied so far; the next update is number step + 1 */
+  int64_t skipped;    /* iterations skipped because of an overflow */
+} ma_scaler_state;
+
+/* Policy of the dynamic loss scale (host struct). */
+typedef struct ma_scaler_config {
+  float backoff;   /* in (0, 1): factor applied on overflow (0.5: halve) */
+  float growth;    /* >= 1: factor applied after `window` clean steps in a row */
+  float min_scale; /* > 0 */
+  float max_scale; /* >= min_scale, finite */
+  int32_t window;  /* >= 1 */
+} ma_scaler_config;
+
 /* ---- housekeeping ---------------------------------------------------------------------- */
 
 /* Library version, major*10000 + minor*100 + patch. */
@@ -175,6 +194,60 @@ int ma_adamw_step_gated(float* p32, float* m, float* v, const void* grad, ma_dty
                         float loss_scale, const ma_norm_result* gate_dev, float max_norm,
                         void* stream);
 
+/* ---- half-precision optimizer states ---------------------------------------------------------- */
+
+/* The same step with p, m and v held in bf16 (Extended Experiments, bf16 half-precision optimizer:
+ * parameters, gradients and both moments move in half precision).  Each element is widened to
+ * fp32, updated exactly as in ma_adamw_step, and stored back by direct truncation (the low 16 bits
+ * of the fp32 result are dropped; a NaN stays a NaN).  p, m, v: bf16 device buffers, updated in
+ * place; the parameter buffer itself is the low-precision copy, so there is no p_lp.
+ * 14 bytes per element instead of 28. */
+int ma_adamw_step_bf16(void* p_bf16, void* m_bf16, void* v_bf16, const void* grad, ma_dtype gdt,
+                       size_t n, const ma_hyper* hyper, int64_t step, float loss_scale,
+                       float clip_coef, void* stream);
+
+/* ma_adamw_step_bf16 with the device-side gate of ma_adamw_step_gated. */
+int ma_adamw_step_bf16_gated(void* p_bf16, void* m_bf16, void* v_bf16, const void* grad,
+                             ma_dtype gdt, size_t n, const ma_hyper* hyper, int64_t step,
+                             float loss_scale, const ma_norm_result* gate_dev, float max_norm,
+                             void* stream);
+
+/* ---- gradient accumulation --------------------------------------------------------------------- */
+
+/* Accumulates one micro-batch gradient into the fp32 flat gradient buffer (Sec. III-C: the flat
+ * buffer is kept in fp32 to support accumulation):
+ *     acc32[i] = first ? widen(grad[i]) : acc32[i] + widen(grad[i])      (one fp32 addition)
+ * grad: MA_BF16, MA_F16 or MA_F32, read only.  The accumulated buffer is then scanned and applied
+ * with gdt = MA_F32. */
+int ma_grad_accumulate(float* acc32, const void* grad, ma_dtype gdt, size_t n, int first,
+                       void* stream);
+
+/* ---- dynamic loss scale on the device ------------------------------------------------------------ */
+
+/* Writes {scale, 0, applied_steps, 0} to *scaler_dev. */
+int ma_scaler_init(ma_scaler_state* scaler_dev, float scale, int64_t applied_steps, void* stream);
+
+/* Advances the state after an iteration whose scan result is *gate_dev:
+ *   overflow:  scale = max(scale * backoff, min_scale); good_steps = 0; skipped += 1
+ *   otherwise: step += 1; good_steps += 1; if good_steps >= window:
+ *              scale = min(scale * growth, max_scale); good_steps = 0
+ * Enqueue it after the update of the same iteration. */
+int ma_scaler_update(ma_scaler_state* scaler_dev, const ma_norm_result* gate_dev,
+                     const ma_scaler_config* cfg, void* stream);
+
+/* ma_overflow_norm with the loss scale read from *scaler_dev on the device. */
+int ma_overflow_norm_auto(const void* grad, ma_dtype gdt, size_t n, const ma_scaler_state* scaler_dev,
+                          ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream);
+
+/* ma_adamw_step_gated with the loss scale and the update number (scaler_dev->step + 1) read on the
+ * device; the bias corrections are evaluated there in fp64.  A whole iteration
+ *   ma_overflow_norm_auto -> ma_adamw_step_auto -> ma_scaler_update
+ * needs no host round trip, whether or not the step is skipped. */
+int ma_adamw_step_auto(float* p32, float* m, float* v, const void* grad, ma_dtype gdt, void* p_lp,
+                       ma_dtype pdt, size_t n, const ma_hyper* hyper,
+                       const ma_scaler_state* scaler_dev, const ma_norm_result* gate_dev,
+                       float max_norm, void* stream);
+
 /* ---- multi-tensor variants (one launch over a whole tensor list) ------------------------------ */
 
 /* Bytes of device memory ma_multi_prepare needs for a list of `count` tensors. */
@@ -200,6 +273,13 @@ int ma_multi_adamw_step(const ma_multi_plan* plan, const ma_hyper* hyper, int64_
 int ma_multi_adamw_step_gated(const ma_multi_plan* plan, const ma_hyper* hyper, int64_t step,
                               float loss_scale, const ma_norm_result* gate_dev, float max_norm,
                               void* stream);
+
+/* The *_auto forms over a prepared tensor list. */
+int ma_multi_overflow_norm_auto(const ma_multi_plan* plan, const ma_scaler_state* scaler_dev,
+                                ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream);
+int ma_multi_adamw_step_auto(const ma_multi_plan* plan, const ma_hyper* hyper,
+                             const ma_scaler_state* scaler_dev, const ma_norm_result* gate_dev,
+                             float max_norm, void* stream);
 
 #ifdef __cplusplus
 }

@@ -37,6 +37,12 @@ class Tensor(ctypes.Structure):
                 ("grad", ctypes.c_void_p), ("p_lp", ctypes.c_void_p), ("n", ctypes.c_size_t)]
 
 
+class ScalerConfig(ctypes.Structure):
+    _fields_ = [("backoff", ctypes.c_float), ("growth", ctypes.c_float),
+                ("min_scale", ctypes.c_float), ("max_scale", ctypes.c_float),
+                ("window", ctypes.c_int32)]
+
+
 class MultiPlanStruct(ctypes.Structure):
     _fields_ = [("table_dev", ctypes.c_void_p), ("entries", ctypes.c_uint64),
                 ("total_elems", ctypes.c_uint64), ("norm_chunks", ctypes.c_uint64),
@@ -69,6 +75,17 @@ def _load() -> ctypes.CDLL:
         "ma_multi_overflow_norm": ([vp, f32, vp, vp, sz, vp], ctypes.c_int),
         "ma_multi_adamw_step": ([vp, vp, i64, f32, f32, vp], ctypes.c_int),
         "ma_multi_adamw_step_gated": ([vp, vp, i64, f32, vp, f32, vp], ctypes.c_int),
+        "ma_adamw_step_bf16": ([vp, vp, vp, vp, i32, sz, vp, i64, f32, f32, vp], ctypes.c_int),
+        "ma_adamw_step_bf16_gated": ([vp, vp, vp, vp, i32, sz, vp, i64, f32, vp, f32, vp],
+                                     ctypes.c_int),
+        "ma_grad_accumulate": ([vp, vp, i32, sz, ctypes.c_int, vp], ctypes.c_int),
+        "ma_scaler_init": ([vp, f32, i64, vp], ctypes.c_int),
+        "ma_scaler_update": ([vp, vp, vp, vp], ctypes.c_int),
+        "ma_overflow_norm_auto": ([vp, i32, sz, vp, vp, vp, sz, vp], ctypes.c_int),
+        "ma_adamw_step_auto": ([vp, vp, vp, vp, i32, vp, i32, sz, vp, vp, vp, f32, vp],
+                               ctypes.c_int),
+        "ma_multi_overflow_norm_auto": ([vp, vp, vp, vp, sz, vp], ctypes.c_int),
+        "ma_multi_adamw_step_auto": ([vp, vp, vp, vp, f32, vp], ctypes.c_int),
     }
     for name, (args, res) in sig.items():
         fn = getattr(lib, name)
@@ -242,3 +259,97 @@ def multi_adamw_step_gated(plan: MultiPlan, h: Hyper, step: int, loss_scale: flo
                            stream=None) -> None:
     _check(lib.ma_multi_adamw_step_gated(ctypes.byref(plan.plan), ctypes.byref(h), int(step),
                                          loss_scale, _slot(gate, index), max_norm, _stream(stream)))
+
+
+# ---- half-precision optimizer states ---------------------------------------------------------
+
+def _bf16_state_args(p, m, v, grad):
+    for t, nm in ((p, "p"), (m, "m"), (v, "v")):
+        if t.dtype != torch.bfloat16:
+            raise TypeError("%s must be bfloat16" % nm)
+    n = p.numel()
+    if not (m.numel() == n and v.numel() == n and grad.numel() == n):
+        raise ValueError("p, m, v and grad must have the same number of elements")
+    return _dev(p, "p"), _dev(m, "m"), _dev(v, "v"), _dev(grad, "grad"), _DT[grad.dtype], n
+
+
+def adamw_step_bf16(p, m, v, grad, h: Hyper, step: int, loss_scale: float = 1.0,
+                    clip: float = 1.0, stream=None) -> None:
+    """ma_adamw_step_bf16: p, m, v held in bf16 and stored back by truncation."""
+    _check(lib.ma_adamw_step_bf16(*_bf16_state_args(p, m, v, grad), ctypes.byref(h), int(step),
+                                  loss_scale, clip, _stream(stream)))
+
+
+def adamw_step_bf16_gated(p, m, v, grad, h: Hyper, step: int, loss_scale: float,
+                          gate: torch.Tensor, max_norm: float, index: int = 0, stream=None) -> None:
+    _check(lib.ma_adamw_step_bf16_gated(*_bf16_state_args(p, m, v, grad), ctypes.byref(h),
+                                        int(step), loss_scale, _slot(gate, index), max_norm,
+                                        _stream(stream)))
+
+
+# ---- gradient accumulation ---------------------------------------------------------------------
+
+def grad_accumulate(acc32: torch.Tensor, grad: torch.Tensor, first: bool, stream=None) -> None:
+    """ma_grad_accumulate: acc32 = grad if first else acc32 + grad (fp32 flat buffer)."""
+    if acc32.dtype != torch.float32:
+        raise TypeError("acc32 must be float32")
+    if acc32.numel() != grad.numel():
+        raise ValueError("acc32 and grad must have the same number of elements")
+    _check(lib.ma_grad_accumulate(_dev(acc32, "acc32"), _dev(grad, "grad"), _DT[grad.dtype],
+                                  grad.numel(), int(bool(first)), _stream(stream)))
+
+
+# ---- dynamic loss scale on the device ------------------------------------------------------------
+
+def scaler_config(backoff=0.5, growth=2.0, min_scale=1.0, max_scale=2.0 ** 24,
+                  window=1000) -> ScalerConfig:
+    return ScalerConfig(backoff, growth, min_scale, max_scale, int(window))
+
+
+def new_scaler(scale: float, applied_steps: int = 0, device="cuda", stream=None) -> torch.Tensor:
+    """One ma_scaler_state (24 bytes) in device memory, as an int64 tensor of 3."""
+    st = torch.zeros(3, dtype=torch.int64, device=device)
+    _check(lib.ma_scaler_init(_dev(st, "scaler"), scale, int(applied_steps), _stream(stream)))
+    return st
+
+
+def read_scaler(st: torch.Tensor):
+    """Synchronising read-back: (scale, good_steps, step, skipped)."""
+    return struct.unpack("<fiqq", st.cpu().numpy().tobytes())
+
+
+def _scaler(st: torch.Tensor) -> int:
+    if st.dtype != torch.int64 or st.numel() < 3:
+        raise TypeError("scaler state must come from new_scaler()")
+    return _dev(st, "scaler")
+
+
+def scaler_update(st: torch.Tensor, gate: torch.Tensor, cfg: ScalerConfig, index: int = 0,
+                  stream=None) -> None:
+    _check(lib.ma_scaler_update(_scaler(st), _slot(gate, index), ctypes.byref(cfg), _stream(stream)))
+
+
+def overflow_norm_auto(grad: torch.Tensor, scaler: torch.Tensor, out: torch.Tensor,
+                       ws: torch.Tensor, index: int = 0, stream=None) -> None:
+    _check(lib.ma_overflow_norm_auto(_dev(grad, "grad"), _DT[grad.dtype], grad.numel(),
+                                     _scaler(scaler), _slot(out, index), _dev(ws, "ws"),
+                                     ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def adamw_step_auto(p, m, v, grad, p_lp, h: Hyper, scaler: torch.Tensor, gate: torch.Tensor,
+                    max_norm: float, index: int = 0, stream=None) -> None:
+    _check(lib.ma_adamw_step_auto(*_step_args(p, m, v, grad, p_lp), ctypes.byref(h),
+                                  _scaler(scaler), _slot(gate, index), max_norm, _stream(stream)))
+
+
+def multi_overflow_norm_auto(plan: MultiPlan, scaler: torch.Tensor, out: torch.Tensor,
+                             ws: torch.Tensor, index: int = 0, stream=None) -> None:
+    _check(lib.ma_multi_overflow_norm_auto(ctypes.byref(plan.plan), _scaler(scaler),
+                                           _slot(out, index), _dev(ws, "ws"),
+                                           ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def multi_adamw_step_auto(plan: MultiPlan, h: Hyper, scaler: torch.Tensor, gate: torch.Tensor,
+                          max_norm: float, index: int = 0, stream=None) -> None:
+    _check(lib.ma_multi_adamw_step_auto(ctypes.byref(plan.plan), ctypes.byref(h), _scaler(scaler),
+                                        _slot(gate, index), max_norm, _stream(stream)))

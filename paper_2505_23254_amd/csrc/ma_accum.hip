@@ -1,0 +1,137 @@
+// Gradient accumulation into the fp32 flat buffer (Sec. III-C: the partition's flat gradient
+// buffer is kept in fp32 so that low-precision micro-batch gradients can be accumulated into it).
+//
+// acc[i] = first ? widen(g[i]) : acc[i] + widen(g[i])  -- one fp32 addition per element.
+// HBM-bound: 2 B read + 4 B written per element for the first micro-batch of an iteration,
+// 2 + 4 read and 4 written afterwards (16-bit gradients).  Same packets, hints and persistent
+// grid as the update kernel.
+
+#include "ma_internal.h"
+
+#ifndef MA_ACCUM_UNROLL
+#define MA_ACCUM_UNROLL 4
+#endif
+#ifndef MA_ACCUM_BLOCKS_PER_CU
+#define MA_ACCUM_BLOCKS_PER_CU 2
+#endif
+
+namespace ma {
+
+constexpr int kAccumUnroll = MA_ACCUM_UNROLL;
+
+template <int GDT>
+__device__ __forceinline__ float accum_grad1(MA_GLOBAL const char* g, uint64_t i) {
+  if constexpr (GDT == kF32) {
+    return reinterpret_cast<MA_GLOBAL const float*>(g)[i];
+  } else {
+    return widen16<GDT>(reinterpret_cast<MA_GLOBAL const uint16_t*>(g)[i]);
+  }
+}
+
+template <int GDT, bool FIRST>
+__device__ __forceinline__ void accum1(MA_GLOBAL float* acc, MA_GLOBAL const char* g, uint64_t i) {
+  const float x = accum_grad1<GDT>(g, i);
+  acc[i] = FIRST ? x : acc[i] + x;
+}
+
+template <int GDT>
+__device__ __forceinline__ f32x4 widen_packet(typename std::conditional<GDT == kF32, f32x4, u32x2>::type r) {
+  if constexpr (GDT == kF32) {
+    return r;
+  } else {
+    f32x4 x;
+    x[0] = widen16<GDT>(r.x & 0xFFFFu);
+    x[1] = widen16<GDT>(r.x >> 16);
+    x[2] = widen16<GDT>(r.y & 0xFFFFu);
+    x[3] = widen16<GDT>(r.y >> 16);
+    return x;
+  }
+}
+
+template <int GDT, bool FIRST>
+__global__ __launch_bounds__(kBlock) void accumulate_kernel(float* acc_, const void* g_, uint64_t n,
+                                                           uint32_t head, uint32_t vec,
+                                                           uint64_t chunks) {
+  using GPacket = typename std::conditional<GDT == kF32, f32x4, u32x2>::type;
+  constexpr uint64_t kChunkGroups = uint64_t(kBlock) * kAccumUnroll;
+  MA_GLOBAL float* acc = to_global(acc_);
+  MA_GLOBAL const char* g = to_global(static_cast<const char*>(g_));
+  const uint32_t tid = threadIdx.x;
+
+  if (!vec) {
+    for (uint64_t i = uint64_t(blockIdx.x) * kBlock + tid; i < n; i += uint64_t(gridDim.x) * kBlock) {
+      accum1<GDT, FIRST>(acc, g, i);
+    }
+    return;
+  }
+  const uint64_t ngroups = (n > head) ? (n - head) / 4 : 0;
+  MA_GLOBAL f32x4* ab = reinterpret_cast<MA_GLOBAL f32x4*>(acc + head);
+  MA_GLOBAL const GPacket* gb =
+      reinterpret_cast<MA_GLOBAL const GPacket*>(g + uint64_t(head) * (GDT == kF32 ? 4 : 2));
+  if (blockIdx.x == 0) {
+    if (tid < head && tid < n) accum1<GDT, FIRST>(acc, g, tid);
+    const uint64_t t0 = uint64_t(head) + ngroups * 4;
+    if (n > head && t0 + tid < n) accum1<GDT, FIRST>(acc, g, t0 + tid);
+  }
+  for (WorkIter<0> w(chunks); w.c < w.end; w.c += w.stride) {
+    const uint64_t g0 = w.c * kChunkGroups + tid;
+    if ((w.c + 1) * kChunkGroups <= ngroups) {
+      GPacket G[kAccumUnroll];
+      f32x4 A[kAccumUnroll];
+#pragma unroll
+      for (int u = 0; u < kAccumUnroll; ++u) {
+        G[u] = ld_stream(gb + g0 + uint64_t(u) * kBlock);
+        if constexpr (!FIRST) A[u] = ld_stream(ab + g0 + uint64_t(u) * kBlock);
+      }
+#pragma unroll
+      for (int u = 0; u < kAccumUnroll; ++u) {
+        const f32x4 x = widen_packet<GDT>(G[u]);
+        st_stream(ab + g0 + uint64_t(u) * kBlock, FIRST ? x : A[u] + x);
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < kAccumUnroll; ++u) {
+        const uint64_t gi = g0 + uint64_t(u) * kBlock;
+        if (gi < ngroups) {
+          const f32x4 x = widen_packet<GDT>(ld_stream(gb + gi));
+          if constexpr (FIRST) {
+            st_stream(ab + gi, x);
+          } else {
+            st_stream(ab + gi, ld_stream(ab + gi) + x);
+          }
+        }
+      }
+    }
+  }
+}
+
+template <int GDT>
+static hipError_t launch_accumulate_g(float* acc, const void* g, uint64_t n, uint32_t head,
+                                      uint32_t vec, int first, uint32_t grid, uint64_t chunks,
+                                      hipStream_t stream) {
+  if (first) {
+    accumulate_kernel<GDT, true><<<grid, kBlock, 0, stream>>>(acc, g, n, head, vec, chunks);
+  } else {
+    accumulate_kernel<GDT, false><<<grid, kBlock, 0, stream>>>(acc, g, n, head, vec, chunks);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_accumulate(float* acc, const void* g, int gdt, uint64_t n, uint32_t head,
+                             uint32_t vec, int first, int device_cus, hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  constexpr uint64_t kChunkElems = uint64_t(kBlock) * 4 * kAccumUnroll;
+  const uint64_t body = (vec && n > head) ? n - head : 0;
+  const uint64_t chunks = vec ? (body + kChunkElems - 1) / kChunkElems : 0;
+  const uint64_t want = uint64_t(device_cus) * MA_ACCUM_BLOCKS_PER_CU;
+  uint64_t blocks = vec ? (chunks < want ? chunks : want) : ((n + kBlock - 1) / kBlock < want ? (n + kBlock - 1) / kBlock : want);
+  if (blocks == 0) blocks = 1;  // head-only or tail-only input: block 0 handles it
+  const uint32_t grid = static_cast<uint32_t>(blocks);
+  switch (gdt) {
+    case kBF16: return launch_accumulate_g<kBF16>(acc, g, n, head, vec, first, grid, chunks, stream);
+    case kF16: return launch_accumulate_g<kF16>(acc, g, n, head, vec, first, grid, chunks, stream);
+    default: return launch_accumulate_g<kF32>(acc, g, n, head, vec, first, grid, chunks, stream);
+  }
+}
+
+}  // namespace ma

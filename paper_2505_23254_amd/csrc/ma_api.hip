@@ -12,6 +12,9 @@
 
 static_assert(sizeof(ma_norm_result) == sizeof(ma::NormResult), "result layout");
 static_assert(sizeof(ma_norm_result) == 16, "result layout");
+static_assert(sizeof(ma_scaler_state) == sizeof(ma::ScalerState) && sizeof(ma_scaler_state) == 24,
+              "scaler state layout");
+static_assert(sizeof(ma_scaler_config) == sizeof(ma::ScalerConfig), "scaler config layout");
 static_assert(int(MA_F32) == ma::kF32 && int(MA_BF16) == ma::kBF16 && int(MA_F16) == ma::kF16,
               "dtype codes");
 
@@ -99,7 +102,8 @@ uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 
 // Fills the alignment-dependent fields of a row and returns its work-item counts.
 // Returns a negative status if a pointer is not aligned to its element size.
-int plan_row(ma::Desc& d, int gdt, bool has_lp, uint64_t* norm_chunks, uint64_t* step_chunks) {
+int plan_row(ma::Desc& d, int gdt, bool has_lp, uint64_t* norm_chunks, uint64_t* step_chunks,
+             size_t sb = 4) {
   const size_t gb = elem_bytes(gdt);
   if (!aligned(d.g, gb)) return fail(MA_ERR_ALIGN, "grad pointer not aligned to its element size");
   // scan: elements before the gradient's first 16-byte boundary
@@ -109,15 +113,16 @@ int plan_row(ma::Desc& d, int gdt, bool has_lp, uint64_t* norm_chunks, uint64_t*
   *norm_chunks = (d.n <= d.norm_head) ? 1 : ceil_div(d.n - d.norm_head, chunk_elems);
 
   if (step_chunks == nullptr) return MA_OK;  // scan-only row
-  if (!aligned(d.p, 4) || !aligned(d.m, 4) || !aligned(d.v, 4))
-    return fail(MA_ERR_ALIGN, "p32/m/v pointers must be 4-byte aligned");
+  if (!aligned(d.p, sb) || !aligned(d.m, sb) || !aligned(d.v, sb))
+    return fail(MA_ERR_ALIGN, "p/m/v pointers must be aligned to their element size");
   if (has_lp && !aligned(d.lp, 2)) return fail(MA_ERR_ALIGN, "p_lp pointer must be 2-byte aligned");
   // update: a head of h elements must bring all five buffers to a 4-element-group boundary
-  const uint32_t h = uint32_t(((16 - (reinterpret_cast<uintptr_t>(d.p) % 16)) % 16) / 4);
+  const uint32_t h =
+      uint32_t(((4 * sb - (reinterpret_cast<uintptr_t>(d.p) % (4 * sb))) % (4 * sb)) / sb);
   auto ok = [&](const void* ptr, size_t eb) {
     return ((reinterpret_cast<uintptr_t>(ptr) + uint64_t(h) * eb) % (4 * eb)) == 0;
   };
-  const bool vec = ok(d.m, 4) && ok(d.v, 4) && ok(d.g, gb) && (!has_lp || ok(d.lp, 2));
+  const bool vec = ok(d.m, sb) && ok(d.v, sb) && ok(d.g, gb) && (!has_lp || ok(d.lp, 2));
   d.step_head = vec ? h : 0;
   d.step_vec = vec ? 1 : 0;
   d.pad = 0;
@@ -144,49 +149,122 @@ int check_plan(const ma_multi_plan* plan) {
   return MA_OK;
 }
 
-int step_common(const ma::Desc* row, const ma_multi_plan* plan, uint64_t chunks, int gdt, int pdt,
-                const ma_hyper* hyper, int64_t step, float loss_scale, float clip_coef,
-                const ma_norm_result* gate, float max_norm, void* stream) {
+struct StepRequest {
+  const ma_hyper* hyper = nullptr;
+  int64_t step = 1;                      // ignored when scaler != nullptr
+  float loss_scale = 1.0f;               // ignored when scaler != nullptr
+  float clip_coef = 1.0f;                // used when gate == nullptr
+  const ma_norm_result* gate = nullptr;  // device gate (gated / auto variants)
+  const void* scaler = nullptr;          // device ma_scaler_state (auto variants)
+  float max_norm = 0.0f;
+  bool gated = false, automatic = false;
+};
+
+int check_request(const StepRequest& q) {
+  if (int rc = check_hyper(q.hyper, q.automatic ? 1 : q.step)) return rc;
+  if (!q.automatic) {
+    if (int rc = check_scale(q.loss_scale)) return rc;
+  } else {
+    if (!q.scaler) return fail(MA_ERR_NULL, "scaler_dev is NULL");
+    if (!aligned(q.scaler, 8)) return fail(MA_ERR_ALIGN, "scaler_dev must be 8-byte aligned");
+  }
+  if (q.gated || q.automatic) {
+    if (!q.gate) return fail(MA_ERR_NULL, "gate_dev is NULL");
+    if (!aligned(q.gate, 8)) return fail(MA_ERR_ALIGN, "gate_dev must be 8-byte aligned");
+    if (std::isnan(q.max_norm)) return fail(MA_ERR_ARG, "max_norm is NaN");
+  } else if (!(q.clip_coef > 0.0f && q.clip_coef <= 1.0f)) {
+    return fail(MA_ERR_ARG, "clip_coef must be in (0, 1] (got %g)", double(q.clip_coef));
+  }
+  return MA_OK;
+}
+
+int step_common(const ma::Desc* row, const ma_multi_plan* plan, uint64_t chunks, int sdt, int gdt,
+                int pdt, const StepRequest& q, void* stream) {
   int cus = 0;
   if (int rc = device_cus(&cus)) return rc;
-  const ma::StepScalars s = host_scalars(*hyper, step, loss_scale, clip_coef);
-  hipError_t e = ma::launch_step(
-      row, plan ? static_cast<const ma::Desc*>(plan->table_dev) : nullptr,
-      plan ? uint32_t(plan->entries) : 1u, chunks, gdt, pdt, s,
-      reinterpret_cast<const ma::NormResult*>(gate), max_norm, loss_scale, cus,
-      static_cast<hipStream_t>(stream));
+  const bool host_gscale = !(q.gated || q.automatic);
+  const ma::StepScalars s = host_scalars(*q.hyper, q.automatic ? 1 : q.step,
+                                         q.automatic ? 1.0f : q.loss_scale,
+                                         host_gscale ? q.clip_coef : 1.0f);
+  ma::StepControl ctl{};
+  ctl.gate = reinterpret_cast<const ma::NormResult*>(q.gate);
+  ctl.scaler = static_cast<const ma::ScalerState*>(q.scaler);
+  ctl.max_norm = q.max_norm;
+  ctl.loss_scale = q.loss_scale;
+  ctl.lr = q.hyper->lr;
+  ctl.bias_correction = q.hyper->bias_correction;
+  hipError_t e = ma::launch_step(row, plan ? static_cast<const ma::Desc*>(plan->table_dev) : nullptr,
+                                 plan ? uint32_t(plan->entries) : 1u, chunks, sdt, gdt, pdt, s, ctl,
+                                 cus, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail_hip(e, "update kernel launch");
   return MA_OK;
 }
 
-int flat_step(float* p32, float* m, float* v, const void* grad, ma_dtype gdt, void* p_lp, ma_dtype pdt,
-              size_t n, const ma_hyper* hyper, int64_t step, float loss_scale, float clip_coef,
-              const ma_norm_result* gate, float max_norm, bool gated, void* stream) {
-  if (int rc = check_hyper(hyper, step)) return rc;
-  if (int rc = check_scale(loss_scale)) return rc;
+// sdt: MA_F32 (fp32 master states, optional 16-bit copy) or MA_BF16 (states held in bf16).
+int flat_step(void* p, void* m, void* v, const void* grad, ma_dtype gdt, void* p_lp, ma_dtype pdt,
+              int sdt, size_t n, const StepRequest& q, void* stream) {
+  if (int rc = check_request(q)) return rc;
   if (!dtype_ok(gdt)) return fail(MA_ERR_DTYPE, "unsupported gradient dtype %d", int(gdt));
   if (p_lp && !(pdt == MA_BF16 || pdt == MA_F16))
     return fail(MA_ERR_DTYPE, "low-precision parameter dtype must be MA_BF16 or MA_F16");
-  if (gated) {
-    if (!gate) return fail(MA_ERR_NULL, "gate_dev is NULL");
-    if (!aligned(gate, 8)) return fail(MA_ERR_ALIGN, "gate_dev must be 8-byte aligned");
-    if (std::isnan(max_norm)) return fail(MA_ERR_ARG, "max_norm is NaN");
-  } else if (!(clip_coef > 0.0f && clip_coef <= 1.0f)) {
-    return fail(MA_ERR_ARG, "clip_coef must be in (0, 1] (got %g)", double(clip_coef));
-  }
   if (n == 0) return MA_OK;
-  if (!p32 || !m || !v || !grad) return fail(MA_ERR_NULL, "p32, m, v and grad must not be NULL");
+  if (!p || !m || !v || !grad) return fail(MA_ERR_NULL, "p, m, v and grad must not be NULL");
   ma::Desc d{};
-  d.p = p32;
-  d.m = m;
-  d.v = v;
+  d.p = static_cast<float*>(p);
+  d.m = static_cast<float*>(m);
+  d.v = static_cast<float*>(v);
   d.g = grad;
   d.lp = p_lp;
   d.n = n;
   uint64_t nc = 0, sc = 0;
-  if (int rc = plan_row(d, gdt, p_lp != nullptr, &nc, &sc)) return rc;
-  return step_common(&d, nullptr, sc, gdt, p_lp ? int(pdt) : ma::kNoLp, hyper, step, loss_scale,
-                     gated ? 1.0f : clip_coef, gated ? gate : nullptr, max_norm, stream);
+  if (int rc = plan_row(d, gdt, p_lp != nullptr, &nc, &sc, sdt == MA_F32 ? 4 : 2)) return rc;
+  return step_common(&d, nullptr, sc, sdt, gdt, p_lp ? int(pdt) : ma::kNoLp, q, stream);
+}
+
+int multi_step(const ma_multi_plan* plan, const StepRequest& q, void* stream) {
+  if (int rc = check_plan(plan)) return rc;
+  if (int rc = check_request(q)) return rc;
+  if (plan->entries == 0) return MA_OK;
+  return step_common(nullptr, plan, plan->step_chunks, MA_F32, plan->gdt, plan->pdt, q, stream);
+}
+
+int norm_common(const ma::Desc* row, const ma_multi_plan* plan, uint64_t chunks, int gdt,
+                float loss_scale, const void* scaler, ma_norm_result* out_dev, void* ws,
+                size_t ws_bytes, void* stream) {
+  if (scaler) {
+    if (!aligned(scaler, 8)) return fail(MA_ERR_ALIGN, "scaler_dev must be 8-byte aligned");
+  } else if (int rc = check_scale(loss_scale)) {
+    return rc;
+  }
+  if (!out_dev) return fail(MA_ERR_NULL, "out_dev is NULL");
+  if (!aligned(out_dev, 8)) return fail(MA_ERR_ALIGN, "out_dev must be 8-byte aligned");
+  if (int rc = check_ws(ws, ws_bytes)) return rc;
+  int cus = 0;
+  if (int rc = device_cus(&cus)) return rc;
+  const double inv = scaler ? 1.0 : 1.0 / (double(loss_scale) * double(loss_scale));
+  hipError_t e = ma::launch_norm(row, plan ? static_cast<const ma::Desc*>(plan->table_dev) : nullptr,
+                                 plan ? uint32_t(plan->entries) : 1u, chunks, gdt, inv,
+                                 static_cast<const ma::ScalerState*>(scaler),
+                                 static_cast<ma::NormPartial*>(ws),
+                                 reinterpret_cast<ma::NormResult*>(out_dev), cus,
+                                 static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail_hip(e, "scan kernel launch");
+  return MA_OK;
+}
+
+int flat_norm(const void* grad, ma_dtype gdt, size_t n, float loss_scale, const void* scaler,
+              bool automatic, ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream) {
+  if (!dtype_ok(gdt)) return fail(MA_ERR_DTYPE, "unsupported gradient dtype %d", int(gdt));
+  if (automatic && !scaler) return fail(MA_ERR_NULL, "scaler_dev is NULL");
+  if (n > 0 && !grad) return fail(MA_ERR_NULL, "grad is NULL");
+  ma::Desc d{};
+  d.g = grad;
+  d.n = n;
+  uint64_t chunks = 0;
+  if (n > 0) {
+    if (int rc = plan_row(d, gdt, false, &chunks, nullptr)) return rc;
+  }
+  return norm_common(&d, nullptr, chunks, gdt, loss_scale, scaler, out_dev, ws, ws_bytes, stream);
 }
 
 }  // namespace
@@ -244,27 +322,7 @@ int ma_plan_tensor(const ma_tensor* t, ma_dtype gdt, uint64_t* norm_items, uint6
 
 int ma_overflow_norm(const void* grad, ma_dtype gdt, size_t n, float loss_scale,
                      ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream) {
-  if (!dtype_ok(gdt)) return fail(MA_ERR_DTYPE, "unsupported gradient dtype %d", int(gdt));
-  if (int rc = check_scale(loss_scale)) return rc;
-  if (!out_dev) return fail(MA_ERR_NULL, "out_dev is NULL");
-  if (!aligned(out_dev, 8)) return fail(MA_ERR_ALIGN, "out_dev must be 8-byte aligned");
-  if (int rc = check_ws(ws, ws_bytes)) return rc;
-  if (n > 0 && !grad) return fail(MA_ERR_NULL, "grad is NULL");
-  ma::Desc d{};
-  d.g = grad;
-  d.n = n;
-  uint64_t chunks = 0;
-  if (n > 0) {
-    if (int rc = plan_row(d, gdt, false, &chunks, nullptr)) return rc;
-  }
-  int cus = 0;
-  if (int rc = device_cus(&cus)) return rc;
-  const double inv = 1.0 / (double(loss_scale) * double(loss_scale));
-  hipError_t e = ma::launch_norm(&d, nullptr, 1, chunks, gdt, inv, static_cast<ma::NormPartial*>(ws),
-                                 reinterpret_cast<ma::NormResult*>(out_dev), cus,
-                                 static_cast<hipStream_t>(stream));
-  if (e != hipSuccess) return fail_hip(e, "scan kernel launch");
-  return MA_OK;
+  return flat_norm(grad, gdt, n, loss_scale, nullptr, false, out_dev, ws, ws_bytes, stream);
 }
 
 int ma_norm_combine(const ma_norm_result* parts_dev, size_t count, ma_norm_result* out_dev,
@@ -285,16 +343,120 @@ int ma_norm_combine(const ma_norm_result* parts_dev, size_t count, ma_norm_resul
 int ma_adamw_step(float* p32, float* m, float* v, const void* grad, ma_dtype gdt, void* p_lp,
                   ma_dtype pdt, size_t n, const ma_hyper* hyper, int64_t step, float loss_scale,
                   float clip_coef, void* stream) {
-  return flat_step(p32, m, v, grad, gdt, p_lp, pdt, n, hyper, step, loss_scale, clip_coef, nullptr,
-                   0.0f, false, stream);
+  StepRequest q;
+  q.hyper = hyper;
+  q.step = step;
+  q.loss_scale = loss_scale;
+  q.clip_coef = clip_coef;
+  return flat_step(p32, m, v, grad, gdt, p_lp, pdt, MA_F32, n, q, stream);
 }
 
 int ma_adamw_step_gated(float* p32, float* m, float* v, const void* grad, ma_dtype gdt, void* p_lp,
                         ma_dtype pdt, size_t n, const ma_hyper* hyper, int64_t step,
                         float loss_scale, const ma_norm_result* gate_dev, float max_norm,
                         void* stream) {
-  return flat_step(p32, m, v, grad, gdt, p_lp, pdt, n, hyper, step, loss_scale, 1.0f, gate_dev,
-                   max_norm, true, stream);
+  StepRequest q;
+  q.hyper = hyper;
+  q.step = step;
+  q.loss_scale = loss_scale;
+  q.gate = gate_dev;
+  q.max_norm = max_norm;
+  q.gated = true;
+  return flat_step(p32, m, v, grad, gdt, p_lp, pdt, MA_F32, n, q, stream);
+}
+
+int ma_adamw_step_auto(float* p32, float* m, float* v, const void* grad, ma_dtype gdt, void* p_lp,
+                       ma_dtype pdt, size_t n, const ma_hyper* hyper,
+                       const ma_scaler_state* scaler_dev, const ma_norm_result* gate_dev,
+                       float max_norm, void* stream) {
+  StepRequest q;
+  q.hyper = hyper;
+  q.gate = gate_dev;
+  q.scaler = scaler_dev;
+  q.max_norm = max_norm;
+  q.automatic = true;
+  return flat_step(p32, m, v, grad, gdt, p_lp, pdt, MA_F32, n, q, stream);
+}
+
+int ma_overflow_norm_auto(const void* grad, ma_dtype gdt, size_t n, const ma_scaler_state* scaler_dev,
+                          ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream) {
+  return flat_norm(grad, gdt, n, 1.0f, scaler_dev, true, out_dev, ws, ws_bytes, stream);
+}
+
+int ma_adamw_step_bf16(void* p, void* m, void* v, const void* grad, ma_dtype gdt, size_t n,
+                       const ma_hyper* hyper, int64_t step, float loss_scale, float clip_coef,
+                       void* stream) {
+  StepRequest q;
+  q.hyper = hyper;
+  q.step = step;
+  q.loss_scale = loss_scale;
+  q.clip_coef = clip_coef;
+  return flat_step(p, m, v, grad, gdt, nullptr, MA_BF16, MA_BF16, n, q, stream);
+}
+
+int ma_adamw_step_bf16_gated(void* p, void* m, void* v, const void* grad, ma_dtype gdt, size_t n,
+                             const ma_hyper* hyper, int64_t step, float loss_scale,
+                             const ma_norm_result* gate_dev, float max_norm, void* stream) {
+  StepRequest q;
+  q.hyper = hyper;
+  q.step = step;
+  q.loss_scale = loss_scale;
+  q.gate = gate_dev;
+  q.max_norm = max_norm;
+  q.gated = true;
+  return flat_step(p, m, v, grad, gdt, nullptr, MA_BF16, MA_BF16, n, q, stream);
+}
+
+int ma_grad_accumulate(float* acc32, const void* grad, ma_dtype gdt, size_t n, int first,
+                       void* stream) {
+  if (!dtype_ok(gdt)) return fail(MA_ERR_DTYPE, "unsupported gradient dtype %d", int(gdt));
+  if (n == 0) return MA_OK;
+  if (!acc32 || !grad) return fail(MA_ERR_NULL, "acc32 and grad must not be NULL");
+  const size_t gb = elem_bytes(gdt);
+  if (!aligned(acc32, 4) || !aligned(grad, gb))
+    return fail(MA_ERR_ALIGN, "acc32 / grad not aligned to their element size");
+  const uint32_t h = uint32_t(((16 - (reinterpret_cast<uintptr_t>(acc32) % 16)) % 16) / 4);
+  const uint32_t vec = ((reinterpret_cast<uintptr_t>(grad) + uint64_t(h) * gb) % (4 * gb)) == 0;
+  int cus = 0;
+  if (int rc = device_cus(&cus)) return rc;
+  hipError_t e = ma::launch_accumulate(acc32, grad, gdt, n, vec ? h : 0, vec, first != 0, cus,
+                                       static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail_hip(e, "accumulate kernel launch");
+  return MA_OK;
+}
+
+int ma_scaler_init(ma_scaler_state* scaler_dev, float scale, int64_t applied_steps, void* stream) {
+  if (!scaler_dev) return fail(MA_ERR_NULL, "scaler_dev is NULL");
+  if (!aligned(scaler_dev, 8)) return fail(MA_ERR_ALIGN, "scaler_dev must be 8-byte aligned");
+  if (int rc = check_scale(scale)) return rc;
+  if (applied_steps < 0) return fail(MA_ERR_ARG, "applied_steps must be >= 0");
+  hipError_t e = ma::launch_scaler_init(reinterpret_cast<ma::ScalerState*>(scaler_dev), scale,
+                                        applied_steps, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail_hip(e, "scaler init launch");
+  return MA_OK;
+}
+
+int ma_scaler_update(ma_scaler_state* scaler_dev, const ma_norm_result* gate_dev,
+                     const ma_scaler_config* cfg, void* stream) {
+  if (!scaler_dev || !gate_dev || !cfg) return fail(MA_ERR_NULL, "scaler_dev, gate_dev and cfg must not be NULL");
+  if (!aligned(scaler_dev, 8) || !aligned(gate_dev, 8))
+    return fail(MA_ERR_ALIGN, "scaler_dev and gate_dev must be 8-byte aligned");
+  if (!(cfg->backoff > 0.0f && cfg->backoff < 1.0f)) return fail(MA_ERR_ARG, "backoff must be in (0, 1)");
+  if (!(cfg->growth >= 1.0f) || !std::isfinite(cfg->growth)) return fail(MA_ERR_ARG, "growth must be finite and >= 1");
+  if (!(cfg->min_scale > 0.0f) || !(cfg->max_scale >= cfg->min_scale) || !std::isfinite(cfg->max_scale))
+    return fail(MA_ERR_ARG, "need 0 < min_scale <= max_scale < inf");
+  if (cfg->window < 1) return fail(MA_ERR_ARG, "window must be >= 1");
+  ma::ScalerConfig c;
+  c.backoff = cfg->backoff;
+  c.growth = cfg->growth;
+  c.min_scale = cfg->min_scale;
+  c.max_scale = cfg->max_scale;
+  c.window = cfg->window;
+  hipError_t e = ma::launch_scaler_update(reinterpret_cast<ma::ScalerState*>(scaler_dev),
+                                          reinterpret_cast<const ma::NormResult*>(gate_dev), c,
+                                          static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return fail_hip(e, "scaler update launch");
+  return MA_OK;
 }
 
 size_t ma_multi_table_bytes(size_t count) { return (count ? count : 1) * sizeof(ma::Desc); }
@@ -368,46 +530,51 @@ int ma_multi_prepare(const ma_tensor* list_host, size_t count, ma_dtype gdt, ma_
 int ma_multi_overflow_norm(const ma_multi_plan* plan, float loss_scale, ma_norm_result* out_dev,
                            void* ws, size_t ws_bytes, void* stream) {
   if (int rc = check_plan(plan)) return rc;
-  if (int rc = check_scale(loss_scale)) return rc;
-  if (!out_dev) return fail(MA_ERR_NULL, "out_dev is NULL");
-  if (!aligned(out_dev, 8)) return fail(MA_ERR_ALIGN, "out_dev must be 8-byte aligned");
-  if (int rc = check_ws(ws, ws_bytes)) return rc;
-  int cus = 0;
-  if (int rc = device_cus(&cus)) return rc;
-  const double inv = 1.0 / (double(loss_scale) * double(loss_scale));
-  hipError_t e = ma::launch_norm(nullptr, static_cast<const ma::Desc*>(plan->table_dev),
-                                 uint32_t(plan->entries), plan->norm_chunks, plan->gdt, inv,
-                                 static_cast<ma::NormPartial*>(ws),
-                                 reinterpret_cast<ma::NormResult*>(out_dev), cus,
-                                 static_cast<hipStream_t>(stream));
-  if (e != hipSuccess) return fail_hip(e, "scan kernel launch");
-  return MA_OK;
+  return norm_common(nullptr, plan, plan->norm_chunks, plan->gdt, loss_scale, nullptr, out_dev, ws,
+                     ws_bytes, stream);
+}
+
+int ma_multi_overflow_norm_auto(const ma_multi_plan* plan, const ma_scaler_state* scaler_dev,
+                                ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream) {
+  if (int rc = check_plan(plan)) return rc;
+  if (!scaler_dev) return fail(MA_ERR_NULL, "scaler_dev is NULL");
+  return norm_common(nullptr, plan, plan->norm_chunks, plan->gdt, 1.0f, scaler_dev, out_dev, ws,
+                     ws_bytes, stream);
 }
 
 int ma_multi_adamw_step(const ma_multi_plan* plan, const ma_hyper* hyper, int64_t step,
                         float loss_scale, float clip_coef, void* stream) {
-  if (int rc = check_plan(plan)) return rc;
-  if (int rc = check_hyper(hyper, step)) return rc;
-  if (int rc = check_scale(loss_scale)) return rc;
-  if (!(clip_coef > 0.0f && clip_coef <= 1.0f))
-    return fail(MA_ERR_ARG, "clip_coef must be in (0, 1] (got %g)", double(clip_coef));
-  if (plan->entries == 0) return MA_OK;
-  return step_common(nullptr, plan, plan->step_chunks, plan->gdt, plan->pdt, hyper, step, loss_scale,
-                     clip_coef, nullptr, 0.0f, stream);
+  StepRequest q;
+  q.hyper = hyper;
+  q.step = step;
+  q.loss_scale = loss_scale;
+  q.clip_coef = clip_coef;
+  return multi_step(plan, q, stream);
 }
 
 int ma_multi_adamw_step_gated(const ma_multi_plan* plan, const ma_hyper* hyper, int64_t step,
                               float loss_scale, const ma_norm_result* gate_dev, float max_norm,
                               void* stream) {
-  if (int rc = check_plan(plan)) return rc;
-  if (int rc = check_hyper(hyper, step)) return rc;
-  if (int rc = check_scale(loss_scale)) return rc;
-  if (!gate_dev) return fail(MA_ERR_NULL, "gate_dev is NULL");
-  if (!aligned(gate_dev, 8)) return fail(MA_ERR_ALIGN, "gate_dev must be 8-byte aligned");
-  if (std::isnan(max_norm)) return fail(MA_ERR_ARG, "max_norm is NaN");
-  if (plan->entries == 0) return MA_OK;
-  return step_common(nullptr, plan, plan->step_chunks, plan->gdt, plan->pdt, hyper, step, loss_scale,
-                     1.0f, gate_dev, max_norm, stream);
+  StepRequest q;
+  q.hyper = hyper;
+  q.step = step;
+  q.loss_scale = loss_scale;
+  q.gate = gate_dev;
+  q.max_norm = max_norm;
+  q.gated = true;
+  return multi_step(plan, q, stream);
+}
+
+int ma_multi_adamw_step_auto(const ma_multi_plan* plan, const ma_hyper* hyper,
+                             const ma_scaler_state* scaler_dev, const ma_norm_result* gate_dev,
+                             float max_norm, void* stream) {
+  StepRequest q;
+  q.hyper = hyper;
+  q.gate = gate_dev;
+  q.scaler = scaler_dev;
+  q.max_norm = max_norm;
+  q.automatic = true;
+  return multi_step(plan, q, stream);
 }
 
 }  // extern "C"

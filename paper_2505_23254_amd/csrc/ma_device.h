@@ -85,6 +85,29 @@ struct NormResult {  // same layout as ma_norm_result
   double sumsq;
 };
 
+// Dynamic loss-scale state in device memory; same layout as ma_scaler_state.
+struct ScalerState {
+  float scale;
+  int32_t good_steps;  // clean steps since the scale last changed
+  int64_t step;        // updates applied so far
+  int64_t skipped;     // iterations skipped because of an overflow
+};
+
+struct ScalerConfig {  // same layout as ma_scaler_config
+  float backoff, growth, min_scale, max_scale;
+  int32_t window;
+};
+
+// What the update kernel reads or derives on the device (every pointer may be null).
+struct StepControl {
+  const NormResult* gate;     // null: the host-side unscale-and-clip factor is final
+  const ScalerState* scaler;  // null: loss scale and update number come from the host
+  float max_norm;
+  float loss_scale;
+  float lr;
+  int32_t bias_correction;
+};
+
 // ---- memory ------------------------------------------------------------------------------
 // Pointers read from a table in memory carry no address-space information, and the compiler
 // would fall back to flat addressing for them.  Every buffer of this library is global device

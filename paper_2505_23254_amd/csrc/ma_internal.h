@@ -18,17 +18,26 @@ namespace ma {
 constexpr uint32_t kMaxNormBlocks = 8192;
 
 // Exactly one of row_host (flat sub-group, row passed by value) and table_dev (tensor list) is
-// non-null.  `chunks` is the number of work items over all rows.
+// non-null.  `chunks` is the number of work items over all rows.  With a scaler state the
+// finalize kernel takes the loss scale from device memory instead of inv_scale_sq.
 hipError_t launch_norm(const Desc* row_host, const Desc* table_dev, uint32_t rows, uint64_t chunks,
-                       int gdt, double inv_scale_sq, NormPartial* partials, NormResult* out,
-                       int device_cus, hipStream_t stream);
+                       int gdt, double inv_scale_sq, const ScalerState* scaler, NormPartial* partials,
+                       NormResult* out, int device_cus, hipStream_t stream);
 
 hipError_t launch_norm_combine(const NormResult* parts, uint32_t count, NormResult* out,
                                hipStream_t stream);
 
-// gate == nullptr: s.gscale is final.  Otherwise the kernel reads the gate on the device.
+// sdt: dtype of p, m, v (kF32, or kBF16 for states stored by truncation).
 hipError_t launch_step(const Desc* row_host, const Desc* table_dev, uint32_t rows, uint64_t chunks,
-                       int gdt, int pdt, const StepScalars& s, const NormResult* gate, float max_norm,
-                       float loss_scale, int device_cus, hipStream_t stream);
+                       int sdt, int gdt, int pdt, const StepScalars& s, const StepControl& ctl,
+                       int device_cus, hipStream_t stream);
+
+hipError_t launch_scaler_init(ScalerState* state, float scale, int64_t step, hipStream_t stream);
+hipError_t launch_scaler_update(ScalerState* state, const NormResult* gate, const ScalerConfig& cfg,
+                                hipStream_t stream);
+
+// acc (fp32) = first ? widen(g) : acc + widen(g) over n elements; head / vec as planned by the host.
+hipError_t launch_accumulate(float* acc, const void* g, int gdt, uint64_t n, uint32_t head,
+                             uint32_t vec, int first, int device_cus, hipStream_t stream);
 
 }  // namespace ma

@@ -172,6 +172,7 @@ __global__ __launch_bounds__(kBlock) void norm_multi_kernel(const Desc* __restri
 // alone.  `threshold` is the sign-stripped pattern of infinity for the gradient format.
 __global__ __launch_bounds__(kBlock) void norm_finalize_kernel(const NormPartial* __restrict__ partials,
                                                               uint32_t count, double inv_scale_sq,
+                                                              const ScalerState* scaler,
                                                               uint32_t threshold, int packed16,
                                                               NormResult* out) {
   __shared__ double s_sum[kBlock / kWave];
@@ -204,6 +205,10 @@ __global__ __launch_bounds__(kBlock) void norm_finalize_kernel(const NormPartial
     NormResult r;
     r.overflow = (m >= threshold) ? 1 : 0;
     r.reserved = 0;
+    if (scaler != nullptr) {
+      const double sc = static_cast<double>(scaler->scale);
+      inv_scale_sq = 1.0 / (sc * sc);
+    }
     r.sumsq = tot * inv_scale_sq;
     *out = r;
   }
@@ -233,8 +238,8 @@ static uint32_t threshold_of(int gdt) {
 }
 
 hipError_t launch_norm(const Desc* row_host, const Desc* table_dev, uint32_t rows, uint64_t chunks,
-                       int gdt, double inv_scale_sq, NormPartial* partials, NormResult* out,
-                       int device_cus, hipStream_t stream) {
+                       int gdt, double inv_scale_sq, const ScalerState* scaler, NormPartial* partials,
+                       NormResult* out, int device_cus, hipStream_t stream) {
   uint64_t want = uint64_t(device_cus) * MA_NORM_BLOCKS_PER_CU;
   if (want > kMaxNormBlocks) want = kMaxNormBlocks;
   const uint32_t grid = static_cast<uint32_t>(chunks < want ? (chunks ? chunks : 1) : want);
@@ -253,8 +258,53 @@ hipError_t launch_norm(const Desc* row_host, const Desc* table_dev, uint32_t row
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  norm_finalize_kernel<<<1, kBlock, 0, stream>>>(partials, grid, inv_scale_sq, threshold_of(gdt),
-                                                 gdt != kF32, out);
+  norm_finalize_kernel<<<1, kBlock, 0, stream>>>(partials, grid, inv_scale_sq, scaler,
+                                                 threshold_of(gdt), gdt != kF32, out);
+  return hipGetLastError();
+}
+
+// ---- dynamic loss scale (Sec. III-C: on overflow the scale factor is reduced) ---------------------
+// One thread; reads the gate, rewrites the 24-byte state.  On overflow: scale *= backoff (not below
+// min_scale), clean-step count restarts, the iteration counts as skipped.  Otherwise the update
+// counts as applied, and after `window` clean steps in a row scale *= growth (not above max_scale).
+__global__ void scaler_update_kernel(ScalerState* state, const NormResult* gate, ScalerConfig cfg) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  ScalerState st = *state;
+  if (gate->overflow != 0) {
+    const float s = st.scale * cfg.backoff;
+    st.scale = s < cfg.min_scale ? cfg.min_scale : s;
+    st.good_steps = 0;
+    st.skipped += 1;
+  } else {
+    st.step += 1;
+    st.good_steps += 1;
+    if (st.good_steps >= cfg.window) {
+      const float s = st.scale * cfg.growth;
+      st.scale = s > cfg.max_scale ? cfg.max_scale : s;
+      st.good_steps = 0;
+    }
+  }
+  *state = st;
+}
+
+__global__ void scaler_init_kernel(ScalerState* state, float scale, int64_t step) {
+  if (threadIdx.x != 0 || blockIdx.x != 0) return;
+  ScalerState st;
+  st.scale = scale;
+  st.good_steps = 0;
+  st.step = step;
+  st.skipped = 0;
+  *state = st;
+}
+
+hipError_t launch_scaler_init(ScalerState* state, float scale, int64_t step, hipStream_t stream) {
+  scaler_init_kernel<<<1, kWave, 0, stream>>>(state, scale, step);
+  return hipGetLastError();
+}
+
+hipError_t launch_scaler_update(ScalerState* state, const NormResult* gate, const ScalerConfig& cfg,
+                                hipStream_t stream) {
+  scaler_update_kernel<<<1, kWave, 0, stream>>>(state, gate, cfg);
   return hipGetLastError();
 }
 

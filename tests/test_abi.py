@@ -153,3 +153,62 @@ def test_work_split_of_a_tensor():
             if same:
                 assert got[4] == 1 and got[3] == (4 - k % 4) % 4
     assert ma.plan_tensor(base, base, base, base, base, 0, ma.MA_BF16) == (0, 0, 0, 0, 0)
+
+
+def test_bf16_state_and_accumulate_argument_errors():
+    f = ma.lib.ma_adamw_step_bf16
+    hb = ctypes.byref(H)
+    assert f(A, A, A, A, ma.MA_BF16, 16, hb, 0, 1.0, 1.0, None) == ma.MA_ERR_ARG
+    assert f(A, A, A, A, ma.MA_BF16, 16, hb, 1, 1.0, 0.0, None) == ma.MA_ERR_ARG
+    assert f(A, A, A, A, 5, 16, hb, 1, 1.0, 1.0, None) == ma.MA_ERR_DTYPE
+    assert f(None, A, A, A, ma.MA_BF16, 16, hb, 1, 1.0, 1.0, None) == ma.MA_ERR_NULL
+    assert f(A + 1, A, A, A, ma.MA_BF16, 16, hb, 1, 1.0, 1.0, None) == ma.MA_ERR_ALIGN
+    assert f(A, A, A + 1, A, ma.MA_BF16, 16, hb, 1, 1.0, 1.0, None) == ma.MA_ERR_ALIGN
+    assert f(A, A, A, A + 2, ma.MA_F32, 16, hb, 1, 1.0, 1.0, None) == ma.MA_ERR_ALIGN
+    assert f(A, A, A, A, ma.MA_BF16, 0, hb, 1, 1.0, 1.0, None) == ma.MA_OK
+    fg = ma.lib.ma_adamw_step_bf16_gated
+    assert fg(A, A, A, A, ma.MA_BF16, 16, hb, 1, 1.0, None, 1.0, None) == ma.MA_ERR_NULL
+    assert fg(A, A, A, A, ma.MA_BF16, 16, hb, 1, 1.0, A + 4, 1.0, None) == ma.MA_ERR_ALIGN
+    assert fg(A, A, A, A, ma.MA_BF16, 16, hb, 1, 1.0, A, float("nan"), None) == ma.MA_ERR_ARG
+    acc = ma.lib.ma_grad_accumulate
+    assert acc(None, A, ma.MA_BF16, 8, 1, None) == ma.MA_ERR_NULL
+    assert acc(A, None, ma.MA_BF16, 8, 1, None) == ma.MA_ERR_NULL
+    assert acc(A + 2, A, ma.MA_BF16, 8, 1, None) == ma.MA_ERR_ALIGN
+    assert acc(A, A + 1, ma.MA_F16, 8, 0, None) == ma.MA_ERR_ALIGN
+    assert acc(A, A + 2, ma.MA_F32, 8, 0, None) == ma.MA_ERR_ALIGN
+    assert acc(A, A, 4, 8, 0, None) == ma.MA_ERR_DTYPE
+    assert acc(A, A, ma.MA_BF16, 0, 0, None) == ma.MA_OK
+
+
+def test_scaler_argument_errors():
+    assert ctypes.sizeof(ma.ScalerConfig) == 20
+    init, upd = ma.lib.ma_scaler_init, ma.lib.ma_scaler_update
+    assert init(None, 1.0, 0, None) == ma.MA_ERR_NULL
+    assert init(A + 4, 1.0, 0, None) == ma.MA_ERR_ALIGN
+    assert init(A, 0.0, 0, None) == ma.MA_ERR_ARG
+    assert init(A, float("inf"), 0, None) == ma.MA_ERR_ARG
+    assert init(A, 1.0, -1, None) == ma.MA_ERR_ARG
+    good = ma.scaler_config()
+    assert upd(None, A, ctypes.byref(good), None) == ma.MA_ERR_NULL
+    assert upd(A, None, ctypes.byref(good), None) == ma.MA_ERR_NULL
+    assert upd(A, A, None, None) == ma.MA_ERR_NULL
+    assert upd(A + 4, A, ctypes.byref(good), None) == ma.MA_ERR_ALIGN
+    for bad in (dict(backoff=0.0), dict(backoff=1.0), dict(growth=0.5), dict(growth=float("inf")),
+                dict(min_scale=0.0), dict(min_scale=4.0, max_scale=2.0), dict(max_scale=float("inf")),
+                dict(window=0)):
+        c = ma.scaler_config(**bad)
+        assert upd(A, A, ctypes.byref(c), None) == ma.MA_ERR_ARG, bad
+    ws = ma.lib.ma_workspace_bytes()
+    na = ma.lib.ma_overflow_norm_auto
+    assert na(A, ma.MA_F16, 8, None, A, A, ws, None) == ma.MA_ERR_NULL
+    assert na(A, ma.MA_F16, 8, A + 4, A, A, ws, None) == ma.MA_ERR_ALIGN
+    assert na(A, ma.MA_F16, 8, A, None, A, ws, None) == ma.MA_ERR_NULL
+    sa = ma.lib.ma_adamw_step_auto
+    hb = ctypes.byref(H)
+    assert sa(A, A, A, A, ma.MA_F16, A, ma.MA_BF16, 8, hb, None, A, 1.0, None) == ma.MA_ERR_NULL
+    assert sa(A, A, A, A, ma.MA_F16, A, ma.MA_BF16, 8, hb, A, None, 1.0, None) == ma.MA_ERR_NULL
+    assert sa(A, A, A, A, ma.MA_F16, A, ma.MA_BF16, 8, None, A, A, 1.0, None) == ma.MA_ERR_NULL
+    assert sa(A, A, A, A, ma.MA_F16, A, ma.MA_F32, 8, hb, A, A, 1.0, None) == ma.MA_ERR_DTYPE
+    plan = ma.MultiPlanStruct()
+    assert ma.lib.ma_multi_overflow_norm_auto(ctypes.byref(plan), A, A, A, ws, None) == ma.MA_ERR_ARG
+    assert ma.lib.ma_multi_adamw_step_auto(ctypes.byref(plan), hb, A, A, 1.0, None) == ma.MA_ERR_ARG

@@ -1,0 +1,341 @@
+"""GPU parity for the rows beyond the basic step: gradient accumulation into the fp32 flat buffer
+(Sec. III-C), the step with bf16 states stored by truncation (Extended Experiments, bf16
+half-precision optimizer) and the dynamic loss scale kept on the device (Sec. III-C).  Same bar as
+the basic step: integer / bit-pattern results exact, fp32 within 2 ulp, sumsq within 1e-5."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_23254_amd import synth
+from tests._util import (MAX_ULP, SUMSQ_RTOL, assert_state_close, host_f32, host_grad, oracle_hyper,
+                         ulp_distance)
+from tests.test_oracle_next import _parse_cases
+
+pytestmark = pytest.mark.gpu
+
+ma = None
+TORCH_DT = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _lib():
+    global ma
+    from paper_2505_23254_amd import binding
+    ma = binding
+    assert torch.cuda.is_available()
+    yield
+
+
+def _hyper(cfg):
+    return ma.hyper(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, 1)
+
+
+def _host_state(st, pdt="bf16"):
+    return dict(p=host_f32(st.p), m=host_f32(st.m), v=host_f32(st.v), lp=synth.bits16(st.p_lp), pdt=pdt)
+
+
+def _micro_grad(n, seed, gdt, scale, device="cuda"):
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    x = torch.empty(n, dtype=torch.float32, device=device).normal_(0.0, 1e-3, generator=gen) * scale
+    return x.to(TORCH_DT[gdt])
+
+
+# ---- gradient accumulation --------------------------------------------------------------------------
+
+ACC_SIZES = [0, 1, 3, 4, 5, 1023, 1024, 4095, 4096, 4097, 8193, 100_003, (1 << 20) + 7]
+
+
+@pytest.mark.parametrize("gdt", ["bf16", "f16", "f32"])
+def test_accumulate_micro_batches(gdt):
+    """Four micro-batches into the fp32 flat buffer: bit-identical to the oracle after each one
+    (one IEEE fp32 addition per element); the first call overwrites whatever the buffer held."""
+    for n in ACC_SIZES:
+        acc = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+        ref = np.full(n, np.nan, np.float32)
+        for k in range(4):
+            g = _micro_grad(n, 1000 + 13 * k + n % 11, gdt, 64.0)
+            g_host = host_grad(g)
+            oracle.grad_accumulate(ref, g_host, gdt, first=(k == 0))
+            ma.grad_accumulate(acc, g, first=(k == 0))
+            assert np.array_equal(host_f32(acc).view(np.uint32), ref.view(np.uint32)), (n, k)
+            assert np.array_equal(host_grad(g), g_host)
+
+
+@pytest.mark.parametrize("off_acc,off_g", [(1, 1), (3, 3), (1, 2), (0, 1), (2, 0), (0, 4)])
+def test_accumulate_misaligned(off_acc, off_g):
+    n = 20_011
+    base = torch.zeros(n + 8, dtype=torch.float32, device="cuda")
+    gbase = _micro_grad(n + 8, 5, "bf16", 1.0)
+    acc, g = base[off_acc:off_acc + n], gbase[off_g:off_g + n]
+    ref = np.zeros(n, np.float32)
+    for k in range(3):
+        oracle.grad_accumulate(ref, host_grad(g), "bf16", first=False)
+        ma.grad_accumulate(acc, g, first=False)
+    assert np.array_equal(host_f32(acc).view(np.uint32), ref.view(np.uint32))
+    full = host_f32(base)
+    assert not full[:off_acc].any() and not full[off_acc + n:].any()      # nothing outside the view
+
+
+def test_accumulated_fp32_buffer_feeds_scan_and_step():
+    """The whole chain of Sec. III-C / IV-A: accumulate fp16 micro-batches into the fp32 buffer,
+    scan it with Algorithm 1's fp32 mask fused with the norm, gate, update."""
+    n, S, micro = 250_003, 4096.0, 3
+    cfg = synth.FlatConfig("t", n, seed=17, m_std=1e-4, v_std=1e-8, step=9, max_norm=0.02)
+    st = synth.make_flat(cfg, device="cuda")
+    ref = _host_state(st)
+    acc = torch.empty(n, dtype=torch.float32, device="cuda")
+    acc_ref = np.empty(n, np.float32)
+    for k in range(micro):
+        g = _micro_grad(n, 300 + k, "f16", S)
+        oracle.grad_accumulate(acc_ref, host_grad(g), "f16", first=(k == 0))
+        ma.grad_accumulate(acc, g, first=(k == 0))
+    ov_ref, ss_ref, c_ref = oracle.optimizer_step(ref["p"], ref["m"], ref["v"], acc_ref, "f32",
+                                                  ref["lp"], "bf16", oracle_hyper(cfg), 9, S, cfg.max_norm)
+    ws, res = ma.workspace(), ma.new_result(2)
+    ma.overflow_norm(acc, S, res, ws)
+    ma.adamw_step_gated(st.p, st.m, st.v, acc, st.p_lp, _hyper(cfg), 9, S, res, cfg.max_norm)
+    ov, ss = ma.read_result(res)
+    assert not ov and not ov_ref and c_ref < 1
+    assert abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref and abs(ss - ss_ref) <= 1e-12 * ss_ref
+    assert_state_close(_host_state(st), ref, "accumulated")
+    # two fp16 values that are finite on their own but overflow the fp32 sum cannot exist (fp16
+    # max is 65504), so an overflow enters the buffer only through an inf/NaN micro-batch entry:
+    g = _micro_grad(n, 999, "f16", S)
+    g.view(torch.int16)[n - 3] = 0x7C00
+    ma.grad_accumulate(acc, g, first=False)
+    ma.overflow_norm(acc, S, res, ws, index=1)
+    assert ma.read_result(res, 1)[0] is True
+
+
+# ---- bf16 optimizer states stored by truncation --------------------------------------------------------
+
+def _bf16_state(cfg, n):
+    """p, m, v as bf16 device tensors (truncated views of the fp32 synthetic state) + host copies."""
+    st = synth.make_flat(cfg, device="cuda", n=n)
+    shift = lambda t: (t.view(torch.int32) >> 16).to(torch.int16).view(torch.bfloat16).contiguous()
+    p, m, v = shift(st.p), shift(st.m), shift(st.v)
+    return st, p, m, v
+
+
+BF_SIZES = [0, 1, 3, 4, 5, 7, 8, 9, 1023, 1024, 4096, 4097, 8191, 100_003, (1 << 20) + 5]
+
+
+@pytest.mark.parametrize("gdt,scale,clip", [("bf16", 1.0, 1.0), ("bf16", 1.0, 0.3), ("f16", 1024.0, 0.5)])
+def test_bf16_state_step_sizes(gdt, scale, clip):
+    for n in BF_SIZES:
+        cfg = synth.FlatConfig("t", n, seed=200 + n % 89, gdt=gdt, loss_scale=scale, m_std=1e-3,
+                               v_std=1e-6, step=7, lr=1e-2, weight_decay=0.1, eps=1e-6)
+        st, p, m, v = _bf16_state(cfg, n)
+        g_host = host_grad(st.g)
+        rp, rm, rv = synth.bits16(p), synth.bits16(m), synth.bits16(v)
+        moved_from = rp.copy()
+        oracle.adamw_step_bf16(rp, rm, rv, g_host, gdt, oracle_hyper(cfg), 7, scale, clip)
+        ma.adamw_step_bf16(p, m, v, st.g, _hyper(cfg), 7, scale, clip)
+        # fp32 arithmetic agrees bit for bit, hence so do the truncated patterns
+        assert np.array_equal(synth.bits16(p), rp), n
+        assert np.array_equal(synth.bits16(m), rm), n
+        assert np.array_equal(synth.bits16(v), rv), n
+        assert np.array_equal(host_grad(st.g), g_host)
+        if n > 1000:
+            assert (rp != moved_from).mean() > 0.5      # the step is large enough to be visible in bf16
+
+
+def test_bf16_state_step_gated_and_skip():
+    n = 70_003
+    cfg = synth.FlatConfig("t", n, seed=23, m_std=1e-3, v_std=1e-6, step=4, lr=1e-2, max_norm=0.05)
+    st, p, m, v = _bf16_state(cfg, n)
+    g_host = host_grad(st.g)
+    rp, rm, rv = synth.bits16(p), synth.bits16(m), synth.bits16(v)
+    ov_ref, ss_ref = oracle.overflow_norm(g_host, "bf16")
+    c_ref = oracle.clip_coef(ss_ref, float(np.float32(cfg.max_norm)))
+    assert not ov_ref and c_ref < 1
+    oracle.adamw_step_bf16(rp, rm, rv, g_host, "bf16", oracle_hyper(cfg), 4, 1.0, float(c_ref))
+    ws, res = ma.workspace(), ma.new_result()
+    ma.overflow_norm(st.g, 1.0, res, ws)
+    ma.adamw_step_bf16_gated(p, m, v, st.g, _hyper(cfg), 4, 1.0, res, cfg.max_norm)
+    assert np.array_equal(synth.bits16(p), rp) and np.array_equal(synth.bits16(m), rm)
+    assert np.array_equal(synth.bits16(v), rv)
+    # overflow: untouched
+    st.g.view(torch.int16)[n // 3] = 0x7F80
+    ma.overflow_norm(st.g, 1.0, res, ws)
+    ma.adamw_step_bf16_gated(p, m, v, st.g, _hyper(cfg), 5, 1.0, res, cfg.max_norm)
+    assert ma.read_result(res)[0] is True
+    assert np.array_equal(synth.bits16(p), rp) and np.array_equal(synth.bits16(m), rm)
+    assert np.array_equal(synth.bits16(v), rv)
+
+
+def test_bf16_state_misaligned():
+    n = 30_001
+    cfg = synth.FlatConfig("t", n + 16, seed=29, m_std=1e-3, v_std=1e-6, step=2, lr=1e-2)
+    st, P, M, V = _bf16_state(cfg, n + 16)
+    for offs in [(1, 1, 1, 1), (3, 3, 3, 3), (1, 2, 3, 0), (0, 0, 0, 2), (4, 4, 4, 4)]:
+        p, m, v, g = (t[o:o + n] for t, o in zip((P, M, V, st.g), offs))
+        rp, rm, rv = synth.bits16(p), synth.bits16(m), synth.bits16(v)
+        edges = [synth.bits16(t) for t in (P, M, V)]
+        oracle.adamw_step_bf16(rp, rm, rv, host_grad(g), "bf16", oracle_hyper(cfg), 2, 1.0, 1.0)
+        ma.adamw_step_bf16(p, m, v, g, _hyper(cfg), 2)
+        for t, r, full, e, o in zip((p, m, v), (rp, rm, rv), (P, M, V), edges, offs):
+            assert np.array_equal(synth.bits16(t), r), offs
+            now = synth.bits16(full)
+            assert np.array_equal(now[:o], e[:o]) and np.array_equal(now[o + n:], e[o + n:])
+
+
+def test_truncation_of_special_values():
+    """Patterns whose truncation is delicate: largest finite stays finite (no rounding up to inf),
+    inf stays inf, NaN with payload only in the dropped half stays NaN.  With lr = 0, beta1 = 0 and a
+    gradient chosen so that m' = g exactly, m carries fp32 values we control into the store."""
+    # m' = 0*m + 1*g with fp32 gradients: any fp32 pattern reaches the truncating store of m
+    pats = np.array([0x3F80FFFF, 0xBF80FFFF, 0x7F7FFFFF, 0x0001FFFF, 0x00008000, 0x7F800000,
+                     0xFF800000, 0x7F800001, 0xFFC12345, 0x80000000, 0x3F808000], np.uint32)
+    n = pats.size
+    g = torch.from_numpy(pats.view(np.float32).copy()).cuda()
+    z = lambda: torch.zeros(n, dtype=torch.bfloat16, device="cuda")
+    p, m, v = z(), z(), z()
+    h = ma.hyper(lr=0.0, beta1=0.0, beta2=0.0, weight_decay=0.0)
+    ma.adamw_step_bf16(p, m, v, g, h, 1)
+    got = synth.bits16(m)
+    want = oracle.truncate_bf16(pats.view(np.float32).copy())
+    nan = np.isnan(pats.view(np.float32)) | (pats == 0x80000000)      # (+0) + (-0) = +0, not g
+    is_nan16 = lambda b: ((b & 0x7F80) == 0x7F80) & ((b & 0x007F) != 0)
+    assert np.array_equal(got[~nan], want[~nan])
+    really_nan = np.isnan(pats.view(np.float32))
+    assert np.all(is_nan16(got[really_nan])) and np.all(is_nan16(want[really_nan]))
+    rp, rm, rv = (np.zeros(n, np.uint16) for _ in range(3))
+    oracle.adamw_step_bf16(rp, rm, rv, pats.view(np.float32).copy(), "f32",
+                           oracle.hyper(lr=0.0, beta1=0.0, beta2=0.0, weight_decay=0.0), 1)
+    # NaNs produced by the arithmetic itself (inf/inf, 0*inf) may differ in sign and payload between
+    # the two machines; their class may not
+    for dev, ref in ((m, rm), (v, rv), (p, rp)):
+        d = synth.bits16(dev)
+        dn = is_nan16(d)
+        assert np.array_equal(dn, is_nan16(ref))
+        assert np.array_equal(d[~dn], ref[~dn])
+
+
+# ---- dynamic loss scale on the device ------------------------------------------------------------------
+
+def _set_gate(res, overflow, sumsq=1.0):
+    raw = np.zeros(2, np.float64)
+    raw.view(np.int32)[0] = int(overflow)
+    raw[1] = sumsq
+    res.copy_(torch.from_numpy(raw))
+
+
+def test_scaler_policy_hand_worked_sequences(golden_dir):
+    for c in _parse_cases(golden_dir + "/loss_scale_sequence.txt"):
+        st = ma.new_scaler(c["scale0"])
+        cfg = ma.scaler_config(*c["cfg"])
+        res = ma.new_result()
+        assert ma.read_scaler(st) == (c["scale0"], 0, 0, 0)
+        for flag, scale, good, step, skipped in c["rows"]:
+            _set_gate(res, flag)
+            ma.scaler_update(st, res, cfg)
+            assert ma.read_scaler(st) == (scale, good, step, skipped), (c["name"], flag)
+
+
+@pytest.mark.parametrize("gdt", ["f16", "bf16"])
+def test_auto_iterations_track_the_oracle(gdt):
+    """Twelve iterations driven entirely from device state (scale, update number, gate): planted
+    overflows skip and halve the scale, clean steps apply update number step+1 with the bias
+    corrections evaluated on the device, growth after three clean steps.  No host round trip is
+    needed between the calls of an iteration; the test reads back only to compare."""
+    n = 60_001
+    S0 = 2048.0
+    cfg = synth.FlatConfig("t", n, seed=31, gdt=gdt, m_std=1e-4, v_std=1e-8, max_norm=0.02)
+    st = synth.make_flat(cfg, device="cuda")
+    ref = _host_state(st)
+    h_ref, h = oracle_hyper(cfg), _hyper(cfg)
+    state_ref, cfg_ref = oracle.scaler_state(scale=S0, step=41), oracle.scaler_cfg(window=3)
+    scaler, scfg = ma.new_scaler(S0, 41), ma.scaler_config(window=3)
+    ws, res = ma.workspace(), ma.new_result()
+    bad_iters = {1, 2, 7}
+    for it in range(12):
+        scale_now = state_ref.scale
+        g = _micro_grad(n, 400 + it, gdt, scale_now)
+        if it in bad_iters:
+            bits = synth.NONFINITE_BITS[gdt][it % 5]
+            g.view(torch.int16)[(it * 7919) % n] = bits - 0x10000 if bits >= 0x8000 else bits
+        g_host = host_grad(g)
+        ov_ref, ss_ref = oracle.optimizer_step_auto(ref["p"], ref["m"], ref["v"], g_host, gdt, ref["lp"],
+                                                    "bf16", h_ref, state_ref, cfg_ref, cfg.max_norm)
+        ma.overflow_norm_auto(g, scaler, res, ws)
+        ma.adamw_step_auto(st.p, st.m, st.v, g, st.p_lp, h, scaler, res, cfg.max_norm)
+        ma.scaler_update(scaler, res, scfg)
+        ov, ss = ma.read_result(res)
+        assert ov == ov_ref == (it in bad_iters), it
+        if not ov:
+            assert abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref and abs(ss - ss_ref) <= 1e-12 * ss_ref
+        assert ma.read_scaler(scaler) == (state_ref.scale, state_ref.good_steps, state_ref.step,
+                                          state_ref.skipped), it
+        assert_state_close(_host_state(st), ref, "iteration %d" % it)
+    assert state_ref.skipped == 3 and state_ref.step == 41 + 9
+
+
+def test_auto_equals_host_driven_gated_step():
+    """The device-evaluated bias corrections equal the host's: an auto step is bit-identical to the
+    gated step given the same scale and update number, at small and large update numbers."""
+    n = 33_333
+    for applied in (0, 1, 99, 9_999, 1_000_000):
+        cfg = synth.FlatConfig("t", n, seed=37, gdt="f16", loss_scale=512.0, m_std=1e-4, v_std=1e-8,
+                               max_norm=0.03)
+        a = synth.make_flat(cfg, device="cuda")
+        b = synth.make_flat(cfg, device="cuda")
+        ws, res = ma.workspace(), ma.new_result()
+        scaler = ma.new_scaler(512.0, applied)
+        ma.overflow_norm_auto(a.g, scaler, res, ws)
+        ma.adamw_step_auto(a.p, a.m, a.v, a.g, a.p_lp, _hyper(cfg), scaler, res, cfg.max_norm)
+        ra = ma.read_result(res)
+        ma.overflow_norm(b.g, 512.0, res, ws)
+        ma.adamw_step_gated(b.p, b.m, b.v, b.g, b.p_lp, _hyper(cfg), applied + 1, 512.0, res, cfg.max_norm)
+        assert ra == ma.read_result(res)
+        for x, y in ((a.p, b.p), (a.m, b.m), (a.v, b.v)):
+            assert ulp_distance(host_f32(x), host_f32(y)).max() <= MAX_ULP
+            assert host_f32(x).tobytes() == host_f32(y).tobytes(), applied
+        assert synth.bits16(a.p_lp).tobytes() == synth.bits16(b.p_lp).tobytes()
+
+
+def test_multi_auto_iteration():
+    shapes = synth.scaled_shapes(synth.llama3_8b_shapes(), 16384, ragged=True)
+    cfg = synth.FlatConfig("t", 0, seed=43, gdt="f16", loss_scale=256.0, m_std=1e-4, v_std=1e-8,
+                           max_norm=0.05)
+    ls = synth.make_list(shapes, cfg, device="cuda")
+    fl = ls.flat
+    ref = dict(p=host_f32(fl.p), m=host_f32(fl.m), v=host_f32(fl.v), lp=synth.bits16(fl.p_lp), pdt="bf16")
+    plan = ma.MultiPlan(ls.p, ls.m, ls.v, ls.g, ls.p_lp)
+    scaler, scfg = ma.new_scaler(256.0, 10), ma.scaler_config(window=100)
+    state_ref, cfg_ref = oracle.scaler_state(scale=256.0, step=10), oracle.scaler_cfg(window=100)
+    ws, res = ma.workspace(), ma.new_result()
+    # the oracle walks the tensors of the list; padding between tensors belongs to no tensor
+    ss_ref = 0.0
+    for g in ls.g:
+        ov, ss = oracle.overflow_norm(host_grad(g), "f16", 256.0)
+        assert not ov
+        ss_ref += ss
+    c_ref = oracle.clip_coef(ss_ref, float(np.float32(cfg.max_norm)))
+    refs = []
+    for i in range(len(shapes)):
+        r = dict(p=host_f32(ls.p[i]), m=host_f32(ls.m[i]), v=host_f32(ls.v[i]), pdt="bf16")
+        r["lp"] = oracle.adamw_step(r["p"], r["m"], r["v"], host_grad(ls.g[i]), "f16", "bf16",
+                                    oracle_hyper(cfg), 11, 256.0, float(c_ref))
+        refs.append(r)
+    oracle.scaler_update(state_ref, cfg_ref, 0)
+    ma.multi_overflow_norm_auto(plan, scaler, res, ws)
+    ma.multi_adamw_step_auto(plan, _hyper(cfg), scaler, res, cfg.max_norm)
+    ma.scaler_update(scaler, res, scfg)
+    ov, ss = ma.read_result(res)
+    assert not ov and abs(ss - ss_ref) <= 1e-12 * ss_ref
+    assert ma.read_scaler(scaler) == (256.0, 1, 11, 0)
+    for i in range(len(shapes)):
+        got = dict(p=host_f32(ls.p[i]), m=host_f32(ls.m[i]), v=host_f32(ls.v[i]), lp=synth.bits16(ls.p_lp[i]))
+        assert_state_close(got, refs[i], "tensor %d" % i)
+    # an overflow skips the list and halves the scale
+    before = host_f32(fl.p).tobytes()
+    ls.g[3].view(torch.int16)[1] = 0x7E00
+    ma.multi_overflow_norm_auto(plan, scaler, res, ws)
+    ma.multi_adamw_step_auto(plan, _hyper(cfg), scaler, res, cfg.max_norm)
+    ma.scaler_update(scaler, res, scfg)
+    assert ma.read_result(res)[0] is True
+    assert ma.read_scaler(scaler) == (128.0, 0, 11, 1)
+    assert host_f32(fl.p).tobytes() == before
