@@ -11,7 +11,7 @@ bounded sample of the same workload.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
 
 Workloads: llama3_8b (default; 290-tensor Llama-3-8B-shaped list, 8.03e9 elements, bf16
-gradients, clip 1.0), flat_1e8, fp16_5e7, c1, qwen14b_4sub (12.57e9 elements as 4 flat
+gradients, clip 1.0; --layout tensor|streams), flat_1e8, fp16_5e7, c1, qwen14b_4sub (12.57e9 elements as 4 flat
 sub-groups streamed on one stream).
 """
 import argparse
@@ -26,7 +26,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-from paper_2505_23254_amd import synth  # noqa: E402
+from paper_2505_23254_amd import hbm, synth  # noqa: E402
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 STEP_BYTES_PER_PARAM = 28.0    # update kernel: read p,m,v (12) + g (2), write p,m,v (12) + p_lp (2)
@@ -38,8 +38,8 @@ SCAN_BYTES_PER_PARAM = 2.0     # scan kernel: read g
 # profiles/hbm_traffic_counters__llama3_8b.txt).  Valid only for the kernel sources they were taken
 # with: when the digest of the kernel sources differs, the figure is reported as null.
 MEASURED_TRAFFIC = {
-    "kernel_sha256": "22437e4c5da565b6384aab671dba479c24ec9f764bb4fcc0eae7fdd4dbf7577f",
-    "llama3_8b": 224856038917,
+    "kernel_sha256": "d8209febd6892a383422b30bab7058e74f64fa9a39de46c496dc0165f67a4a7a",
+    "llama3_8b": 224855360654,
 }
 
 
@@ -68,8 +68,14 @@ def log(*a):
 class Workload:
     """Holds device state and enqueues one step; records (scan, update) event pairs."""
 
-    def __init__(self, name, ma):
-        self.name, self.ma = name, ma
+    def __init__(self, name, ma, layout="streams", placement="region"):
+        self.name, self.ma, self.layout, self.placement = name, ma, "flat", placement
+        # placement "region": the state is cut from one whole-device allocation at the offset
+        # that splits its traffic evenly over two of the three 96 GiB HBM regions (hbm.py);
+        # "plain": a fresh allocation of just the state's size, wherever the driver puts it
+        self.device_arena = hbm.DeviceArena("cuda") if placement == "region" else None
+        place = (lambda nbytes, traffic: self.device_arena.window(nbytes, traffic)) \
+            if self.device_arena else (lambda nbytes, traffic: None)
         self.ws = ma.workspace()
         self.res = ma.new_result()
         self.t = 100
@@ -77,18 +83,23 @@ class Workload:
         if name == "llama3_8b":
             cfg = synth.FlatConfig(name, 0, seed=3, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
             self.cfg = cfg
-            self.state = synth.make_list(synth.llama3_8b_shapes(), cfg, device="cuda")
+            self.layout = layout
+            shapes = synth.llama3_8b_shapes()
+            self.state = synth.make_list(shapes, cfg, device="cuda", layout=layout,
+                                         arena=place(synth.list_state_bytes(shapes, layout),
+                                                     synth.list_traffic(shapes, layout)))
             self.plan = ma.MultiPlan(self.state.p, self.state.m, self.state.v, self.state.g,
                                      self.state.p_lp)
             self.n = self.plan.total
             self.kind = "multi"
             self.desc = ("290-tensor Llama-3-8B-shaped list, %d elements, fp32 p/m/v, bf16 grads "
-                         "~N(0,1e-3), clip 1.0" % self.n)
+                         "~N(0,1e-3), clip 1.0; layout '%s', placement '%s'" % (self.n, layout, placement))
         elif name == "qwen14b_4sub":
             cfg = synth.FlatConfig(name, 0, seed=4, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
             self.cfg = cfg
             total = sum(n for _, n in synth.qwen14b_class_shapes())
-            self.flat = synth.make_flat(cfg, device="cuda", n=total)
+            self.flat = synth.make_flat(cfg, device="cuda", n=total,
+                                        arena=place(synth.flat_state_bytes(total), synth.flat_traffic(total)))
             self.n = total
             self.kind = "sub"
             self.parts = ma.new_result(4)
@@ -97,7 +108,8 @@ class Workload:
         else:
             cfg = synth.config({"flat_1e8": "c2", "fp16_5e7": "c3a", "c1": "c1"}[name])
             self.cfg = cfg
-            self.flat = synth.make_flat(cfg, device="cuda")
+            self.flat = synth.make_flat(cfg, device="cuda",
+                                        arena=place(synth.flat_state_bytes(cfg.n), synth.flat_traffic(cfg.n)))
             self.n = cfg.n
             self.t = cfg.step
             self.kind = "flat"
@@ -146,7 +158,11 @@ def cpu_baseline(wl, sample_elems, passes):
     import numpy as np
     import oracle
     c = wl.cfg
-    src = wl.state.flat if wl.kind == "multi" else wl.flat
+    if wl.kind == "multi":      # the list's first tensor (the embedding) is larger than any sample
+        st = wl.state
+        src = synth.FlatState(st.p[0], st.m[0], st.v[0], st.g[0], st.p_lp[0])
+    else:
+        src = wl.flat
     n = min(sample_elems, src.p.numel())
     p, m, v = (t[:n].cpu().numpy().copy() for t in (src.p, src.m, src.v))
     g = synth.bits16(src.g[:n])
@@ -184,6 +200,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama3_8b",
                     choices=["llama3_8b", "flat_1e8", "fp16_5e7", "c1", "qwen14b_4sub"])
+    ap.add_argument("--layout", default="streams", choices=["streams", "tensor"],
+                    help="llama3_8b only: how the list's buffers lie in the state: 'streams' = five flat "
+                         "buffers p|m|v|g|p_lp (default), 'tensor' = the five buffers of each tensor adjacent")
+    ap.add_argument("--placement", default="region", choices=["region", "plain"],
+                    help="'region' (default): cut the state from one whole-device allocation so that its "
+                         "traffic splits evenly over two 96 GiB HBM regions; 'plain': a fresh allocation")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 28)
     ap.add_argument("--cpu-passes", type=int, default=4)
@@ -201,7 +223,7 @@ def main():
 
     torch.cuda.set_device(0)
     t_setup = time.perf_counter()
-    wl = Workload(args.workload, ma)
+    wl = Workload(args.workload, ma, args.layout, args.placement)
     torch.cuda.synchronize()
     log("setup %.1f s: %s" % (time.perf_counter() - t_setup, wl.desc))
 
@@ -216,8 +238,17 @@ def main():
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     if args.copy_calibration > 0:
-        src = torch.ones(args.copy_calibration, dtype=torch.uint8, device="cuda")
-        dst = torch.empty_like(src)
+        nb = args.copy_calibration
+        if wl.device_arena is not None:      # the arena holds the device's memory: use its unused tail
+            buf, state = wl.device_arena.buf, (wl.state.arena if wl.kind == "multi" else wl.flat.arena)
+            tail = buf.numel() - (state.data_ptr() - buf.data_ptr() + state.numel())
+            if tail < 2 * nb:
+                sys.exit("bench.py: --copy-calibration needs %d free bytes behind the state" % (2 * nb))
+            src, dst = buf[-2 * nb:-nb], buf[-nb:]
+            src.fill_(1)
+        else:
+            src = torch.ones(nb, dtype=torch.uint8, device="cuda")
+            dst = torch.empty_like(src)
         torch.cuda.synchronize()
         dst.copy_(src)
         torch.cuda.synchronize()
@@ -241,6 +272,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "description": wl.desc, "elements": wl.n,
+                   "layout": wl.layout, "placement": wl.placement,
                    "grad_dtype": wl.cfg.gdt, "param_copy_dtype": wl.cfg.pdt,
                    "max_norm": wl.cfg.max_norm, "loss_scale": wl.cfg.loss_scale,
                    "sumsq_last_step": ss},

@@ -1,0 +1,70 @@
+"""Where optimizer state lies in the 288 GiB of HBM of one MI355X.
+
+Measured on MI355X (two-stream write and mixed read/write probes over a whole-device allocation):
+
+* the HBM behaves as three regions of 96 GiB each.  Streams that lie in ONE region share a lower
+  ceiling (two write streams: ~5.7 TB/s inside a region, ~7.1 TB/s across two regions; the 1:1
+  read/write mix of the update kernel: ~5.3 TB/s inside one region);
+* one allocation that takes (nearly) all free device memory maps linearly onto the regions: byte
+  offset x of the allocation lies in region x // 96 GiB;
+* the update kernel is fastest when its traffic splits evenly over two regions (measured on the
+  8B-shaped state: 6.37 TB/s with the state straddling a region boundary half and half, 5.85-6.0
+  TB/s with 80 % of it inside one region; three-way splits were not better than the even two-way
+  split).
+
+Hence this helper: take the device's free memory as one arena and hand out, for a state of a given
+size, the window of the arena whose traffic midpoint sits on a region boundary.  Only placement
+lives here; nothing of the optimizer step.
+"""
+from typing import Optional, Sequence, Tuple
+
+import torch
+
+GIB = 1 << 30
+REGION_BYTES = 96 * GIB
+ALIGN = 2 << 20
+
+
+class DeviceArena:
+    """All free memory of one device as a single allocation (minus `reserve_gib` left to others)."""
+
+    def __init__(self, device="cuda", reserve_gib: float = 3.0):
+        dev = torch.device(device)
+        free, _ = torch.cuda.mem_get_info(dev)
+        nbytes = (int(free - reserve_gib * GIB) // ALIGN) * ALIGN
+        if nbytes <= 0:
+            raise RuntimeError("no free device memory for an arena")
+        self.buf = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+
+    @property
+    def nbytes(self) -> int:
+        return self.buf.numel()
+
+    def window(self, nbytes: int,
+               traffic: Optional[Sequence[Tuple[int, float]]] = None) -> torch.Tensor:
+        """A uint8 view of `nbytes` bytes placed so that half of the traffic falls on each side of a
+        region boundary.  `traffic`: (bytes, weight) of the state's pieces in address order, weight =
+        bytes moved per byte stored (2 for a buffer read and written, 1 for read-only or write-only);
+        None = uniform.  A state larger than two regions is centred on the middle region instead."""
+        if nbytes > self.nbytes:
+            raise ValueError("state of %d bytes does not fit the arena of %d" % (nbytes, self.nbytes))
+        if nbytes > 2 * REGION_BYTES:
+            start = REGION_BYTES + REGION_BYTES // 2 - nbytes // 2
+        else:
+            start = REGION_BYTES - self._midpoint(nbytes, traffic)
+        start = max(0, min(start, self.nbytes - nbytes))
+        start = start // ALIGN * ALIGN
+        return self.buf[start:start + nbytes]
+
+    @staticmethod
+    def _midpoint(nbytes: int, traffic) -> int:
+        if not traffic:
+            return nbytes // 2
+        total = sum(b * w for b, w in traffic)
+        acc, off = 0.0, 0
+        for b, w in traffic:
+            if b * w > 0 and acc + b * w >= total / 2:
+                return off + int((total / 2 - acc) / w)
+            acc += b * w
+            off += b
+        return nbytes // 2

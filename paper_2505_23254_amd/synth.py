@@ -115,30 +115,56 @@ def plant_nonfinite(g: torch.Tensor, gdt: str, count: int, seed: int) -> List[in
 ARENA_ALIGN = 2 << 20   # every buffer of a state starts on a 2 MiB boundary of the arena
 
 
-def carve_state(n: int, gdt: str, pdt: str, device: str):
-    """One allocation for a whole optimizer state, cut into p | m | v | g | p_lp in that order.
-
-    A single arena keeps the five streams of the update kernel at fixed, known distances from
-    each other (the kernel's speed depends on where the streams lie relative to each other in
-    HBM, and one allocation makes that reproducible from process to process).
-    """
+def _flat_layout(n: int):
     sizes = [4 * n, 4 * n, 4 * n, 2 * n, 2 * n]
     offs, total = [], 0
     for sz in sizes:
         offs.append(total)
         total += (sz + ARENA_ALIGN - 1) // ARENA_ALIGN * ARENA_ALIGN
-    arena = torch.empty(max(total, 1), dtype=torch.uint8, device=device)
+    return offs, sizes, max(total, 1)
+
+
+def flat_state_bytes(n: int) -> int:
+    """Bytes carve_state needs for n elements."""
+    return _flat_layout(n)[2]
+
+
+def flat_traffic(n: int):
+    """(bytes, bytes moved per byte stored) of the five pieces in address order: p, m, v are read
+    and written by the update, the gradient is only read, the parameter copy only written."""
+    offs, _, total = _flat_layout(n)
+    ends = offs[1:] + [total]
+    return [(e - o, w) for o, e, w in zip(offs, ends, (2.0, 2.0, 2.0, 1.0, 1.0))]
+
+
+def carve_state(n: int, gdt: str, pdt: str, device: str, arena: Optional[torch.Tensor] = None):
+    """One allocation for a whole optimizer state, cut into p | m | v | g | p_lp in that order.
+
+    A single arena keeps the five streams of the update kernel at fixed, known distances from
+    each other (the kernel's speed depends on where the streams lie in HBM, and one allocation
+    makes that reproducible from process to process).  `arena`: an existing uint8 device buffer
+    of at least flat_state_bytes(n) bytes to cut from, instead of a new allocation.
+    """
+    offs, sizes, total = _flat_layout(n)
+    if arena is None:
+        arena = torch.empty(total, dtype=torch.uint8, device=device)
+    elif arena.dtype != torch.uint8 or arena.numel() < total:
+        raise ValueError("arena must be a uint8 buffer of at least %d bytes" % total)
     dts = [torch.float32, torch.float32, torch.float32, _TORCH_LP[gdt], _TORCH_LP[pdt]]
     views = [arena[o:o + sz].view(dt) for o, sz, dt in zip(offs, sizes, dts)]
     return arena, views
 
 
-def make_flat(cfg: FlatConfig, device: str = "cpu", n: Optional[int] = None) -> FlatState:
-    """Allocate and fill one flat sub-group on `device` (n overrides cfg.n for small cases)."""
+def make_flat(cfg: FlatConfig, device: str = "cpu", n: Optional[int] = None,
+              arena: Optional[torch.Tensor] = None) -> FlatState:
+    """Allocate (or cut from `arena`) and fill one flat sub-group on `device` (n overrides cfg.n
+    for small cases)."""
     n = cfg.n if n is None else n
+    if arena is not None:
+        device = arena.device
     gen = torch.Generator(device=device)
     gen.manual_seed(cfg.seed)
-    arena, (p, m, v, g, p_lp) = carve_state(n, cfg.gdt, cfg.pdt, device)
+    arena, (p, m, v, g, p_lp) = carve_state(n, cfg.gdt, cfg.pdt, device, arena)
     _fill_normal(p, cfg.p_std, gen)
     m.zero_()
     if cfg.m_std > 0:
@@ -208,30 +234,104 @@ class ListState:
     v: List[torch.Tensor]
     g: List[torch.Tensor]
     p_lp: List[torch.Tensor]
-    flat: Optional[FlatState] = None     # the one allocation the views are cut from
+    flat: Optional[FlatState] = None     # layout "streams": the flat buffers the views are cut from
+    arena: Optional[torch.Tensor] = None  # layout "tensor": the one allocation behind all views
 
     @property
     def total(self) -> int:
         return sum(t.numel() for t in self.p)
 
 
-def make_list(shapes: List[Tuple[str, int]], cfg: FlatConfig, device: str = "cpu",
-              align_elems: int = 64) -> ListState:
-    """Fill one flat allocation per state and cut per-tensor views from it.
+def _round_up(x: int, a: int) -> int:
+    return (x + a - 1) // a * a
 
-    Each tensor starts at a multiple of `align_elems` elements (as separately allocated
-    framework tensors would); align_elems=1 packs them back to back, which misaligns most
-    tensors when their sizes are ragged.
-    """
+
+def _list_offsets(shapes, align_elems: int):
     offs, total = [], 0
     for _, numel in shapes:
-        total = (total + align_elems - 1) // align_elems * align_elems
+        total = _round_up(total, align_elems)
         offs.append(total)
         total += numel
-    flat = make_flat(cfg, device=device, n=total)
-    cut = lambda buf: [buf[o:o + numel] for o, (_, numel) in zip(offs, shapes)]
-    return ListState([s[0] for s in shapes], cut(flat.p), cut(flat.m), cut(flat.v), cut(flat.g),
-                     cut(flat.p_lp), flat)
+    return offs, total
+
+
+def _tensor_places(shapes):
+    elem = (4, 4, 4, 2, 2)
+    places, total = [], 0
+    for _, numel in shapes:
+        row = []
+        for eb in elem:
+            nbytes = eb * numel
+            total = _round_up(total, ARENA_ALIGN if nbytes >= ARENA_ALIGN else 4096)
+            row.append((total, nbytes))
+            total += nbytes
+        places.append(row)
+    return places, max(total, 1)
+
+
+def list_state_bytes(shapes: List[Tuple[str, int]], layout: str = "streams", align_elems: int = 64) -> int:
+    """Bytes make_list needs for this list and layout."""
+    if layout == "streams":
+        return flat_state_bytes(_list_offsets(shapes, align_elems)[1])
+    return _tensor_places(shapes)[1]
+
+
+def list_traffic(shapes: List[Tuple[str, int]], layout: str = "streams", align_elems: int = 64):
+    """Traffic weights of the list's pieces in address order (None: uniform)."""
+    if layout == "streams":
+        return flat_traffic(_list_offsets(shapes, align_elems)[1])
+    return None
+
+
+def make_list(shapes: List[Tuple[str, int]], cfg: FlatConfig, device: str = "cpu",
+              align_elems: int = 64, layout: str = "streams",
+              arena: Optional[torch.Tensor] = None) -> ListState:
+    """A tensor list in one allocation (a new one, or the front of the uint8 buffer `arena`).
+
+    layout "streams": five flat buffers p | m | v | g | p_lp, each tensor a view at its running
+    offset.  Each tensor starts at a multiple of `align_elems` elements; align_elems=1 packs them
+    back to back, which misaligns most tensors when their sizes are ragged.
+
+    layout "tensor": the five buffers of ONE tensor lie next to each other, tensor after tensor
+    (p_k | m_k | v_k | g_k | p_lp_k), as when a framework allocates a parameter together with its
+    gradient and optimizer states.  Buffers of 2 MiB or more start on a 2 MiB boundary, smaller
+    ones on a 4 KiB boundary.
+    """
+    if layout == "streams":
+        offs, total = _list_offsets(shapes, align_elems)
+        flat = make_flat(cfg, device=device, n=total, arena=arena)
+        cut = lambda buf: [buf[o:o + numel] for o, (_, numel) in zip(offs, shapes)]
+        return ListState([s[0] for s in shapes], cut(flat.p), cut(flat.m), cut(flat.v), cut(flat.g),
+                         cut(flat.p_lp), flat, flat.arena)
+    if layout != "tensor":
+        raise ValueError("layout must be 'streams' or 'tensor'")
+    dts = (torch.float32, torch.float32, torch.float32, _TORCH_LP[cfg.gdt], _TORCH_LP[cfg.pdt])
+    places, total = _tensor_places(shapes)
+    if arena is None:
+        arena = torch.empty(total, dtype=torch.uint8, device=device)
+    elif arena.dtype != torch.uint8 or arena.numel() < total:
+        raise ValueError("arena must be a uint8 buffer of at least %d bytes" % total)
+    device = arena.device
+    gen = torch.Generator(device=device)
+    gen.manual_seed(cfg.seed)
+    out = ListState([s[0] for s in shapes], [], [], [], [], [], None, arena)
+    for row in places:
+        p, m, v, g, p_lp = (arena[o:o + nb].view(dt) for (o, nb), dt in zip(row, dts))
+        _fill_normal(p, cfg.p_std, gen)
+        m.zero_()
+        if cfg.m_std > 0:
+            _fill_normal(m, cfg.m_std, gen)
+        v.zero_()
+        if cfg.v_std > 0:
+            _fill_normal(v, cfg.v_std, gen)
+            v.abs_()
+        _fill_grad(g, cfg.g_std, cfg.loss_scale, gen)
+        piece = 1 << 27
+        for a in range(0, p.numel(), piece):
+            p_lp[a:a + piece].copy_(p[a:a + piece])
+        for lst, t in zip((out.p, out.m, out.v, out.g, out.p_lp), (p, m, v, g, p_lp)):
+            lst.append(t)
+    return out
 
 
 def bits16(t: torch.Tensor):

@@ -212,3 +212,55 @@ def test_scaler_argument_errors():
     plan = ma.MultiPlanStruct()
     assert ma.lib.ma_multi_overflow_norm_auto(ctypes.byref(plan), A, A, A, ws, None) == ma.MA_ERR_ARG
     assert ma.lib.ma_multi_adamw_step_auto(ctypes.byref(plan), hb, A, A, 1.0, None) == ma.MA_ERR_ARG
+
+
+def test_region_window_placement():
+    """Host logic of the HBM placement helper: the traffic midpoint of a state lands on the boundary
+    between the first two 96 GiB regions; very large states are centred on the middle region."""
+    from paper_2505_23254_amd import hbm, synth
+    G = hbm.GIB
+    mid = hbm.DeviceArena._midpoint
+    assert mid(120 * G, None) == 60 * G
+    # p, m, v (read + written) then g, p_lp (one direction): half of 28 units lies 6/8 into m
+    n = 1 << 30
+    tr = synth.flat_traffic(n)
+    assert [w for _, w in tr] == [2.0, 2.0, 2.0, 1.0, 1.0]
+    assert sum(b for b, _ in tr) == synth.flat_state_bytes(n)
+    assert mid(synth.flat_state_bytes(n), tr) == 4 * n + 3 * n
+    shapes = synth.llama3_8b_shapes()
+    assert synth.list_state_bytes(shapes, "streams") == synth.flat_state_bytes(8_030_257_152)
+    assert synth.list_state_bytes(shapes, "tensor") >= 14 * 8_030_257_152
+    assert synth.list_traffic(shapes, "tensor") is None
+
+    class Fake(hbm.DeviceArena):
+        def __init__(self, nbytes):
+            self.buf = np.empty(0)
+            self._n = nbytes
+
+        @property
+        def nbytes(self):
+            return self._n
+
+        def window(self, nbytes, traffic=None):      # same arithmetic, returns the start offset
+            self.buf = _Span(self._n)
+            return super().window(nbytes, traffic)
+
+    class _Span:
+        def __init__(self, n):
+            self.n = n
+
+        def numel(self):
+            return self.n
+
+        def __getitem__(self, sl):
+            return sl.start, sl.stop
+
+    a = Fake(283 * G)
+    s, e = a.window(120 * G)
+    assert (s, e) == (36 * G, 156 * G)
+    s, e = a.window(200 * G)                           # larger than two regions: centred on 144 GiB
+    assert (s + e) // 2 == 144 * G
+    s, e = a.window(280 * G)
+    assert s >= 0 and e <= 283 * G
+    with pytest.raises(ValueError):
+        a.window(284 * G)

@@ -11,7 +11,7 @@ import pytest
 import torch
 
 import oracle
-from paper_2505_23254_amd import synth
+from paper_2505_23254_amd import hbm, synth
 from tests._util import SUMSQ_RTOL, assert_state_close, host_f32, host_grad, oracle_hyper
 
 pytestmark = pytest.mark.gpu
@@ -134,19 +134,59 @@ def _list_ranges(shapes, total, seed, n_random):
     return ranges
 
 
-def test_llama3_8b_list_sampled():
+def _tensor_ranges(shapes, seed, n_random):
+    """Per tensor: first and last EDGE elements; plus seeded random blocks inside random tensors."""
+    per = [[(0, EDGE), (n - EDGE, n)] for _, n in shapes]
+    rng = np.random.default_rng(seed)
+    sizes = np.array([n for _, n in shapes], dtype=np.float64)
+    for i in rng.choice(len(shapes), n_random, p=sizes / sizes.sum()).tolist():
+        n = shapes[i][1]
+        a = int(rng.integers(0, max(1, n - EDGE)))
+        per[i].append((a, a + EDGE))
+    return [_merge(r, shapes[i][1]) for i, r in enumerate(per)]
+
+
+def _gather_list(tensors, per):
+    return torch.cat([t[a:b] for t, r in zip(tensors, per) for a, b in r])
+
+
+def _sample_list(ls, per, pdt):
+    return dict(p=host_f32(_gather_list(ls.p, per)), m=host_f32(_gather_list(ls.m, per)),
+                v=host_f32(_gather_list(ls.v, per)), lp=synth.bits16(_gather_list(ls.p_lp, per)), pdt=pdt)
+
+
+def _checksums_list(ls):
+    out = []
+    for lst in (ls.p, ls.m, ls.v, ls.p_lp):
+        out.append(sum(int(t.view(torch.int32 if t.element_size() == 4 else torch.int16).sum(dtype=torch.int64))
+                       for t in lst))
+    return out
+
+
+@pytest.mark.parametrize("layout", ["streams", "tensor"])
+def test_llama3_8b_list_sampled(layout):
     """The benchmark workload itself: 290 tensors, 8,030,257,152 elements, one scan launch and one
-    gated update launch."""
+    gated update launch; in the arena layout the benchmark times ("tensor": the five buffers of a
+    tensor adjacent) and with five flat buffers ("streams")."""
     _need_gib(135)
     shapes = synth.llama3_8b_shapes()
     cfg = synth.FlatConfig("llama3_8b", 0, seed=3, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
-    ls = synth.make_list(shapes, cfg, device="cuda")
-    fl, total = ls.flat, ls.flat.p.numel()
-    assert total == 8_030_257_152                      # no padding between the views
-    ranges = _merge(_list_ranges(shapes, total, 17, 1200), total)
-    before = _sample_state(fl, ranges, "bf16")
-    g_s = host_grad(_gather(fl.g, ranges))
-    ov_ref, ss_ref = _oracle_norm_all(fl.g, "bf16", 1.0)
+    # placed as the benchmark places it: cut from a whole-device allocation, traffic split evenly
+    # over two HBM regions
+    device_arena = hbm.DeviceArena("cuda", reserve_gib=12)      # the checks below need temporaries
+    window = device_arena.window(synth.list_state_bytes(shapes, layout), synth.list_traffic(shapes, layout))
+    ls = synth.make_list(shapes, cfg, device="cuda", layout=layout, arena=window)
+    assert ls.arena.data_ptr() == window.data_ptr()
+    assert ls.total == 8_030_257_152
+    if layout == "streams":
+        assert ls.flat.p.numel() == ls.total               # no padding between the views
+    per = _tensor_ranges(shapes, 17, 1200)
+    before = _sample_list(ls, per, "bf16")
+    g_s = host_grad(_gather_list(ls.g, per))
+    ov_ref, ss_ref = False, 0.0
+    for g in ls.g:                                         # flag and sum over ALL elements
+        o, s_ = _oracle_norm_all(g, "bf16", 1.0)
+        ov_ref, ss_ref = ov_ref or o, ss_ref + s_
     c_ref = oracle.clip_coef(ss_ref, 1.0)
     assert not ov_ref and 0.005 < c_ref < 0.02         # norm ~ 90
     before["lp"] = oracle.adamw_step(before["p"], before["m"], before["v"], g_s, "bf16", "bf16",
@@ -158,14 +198,14 @@ def test_llama3_8b_list_sampled():
     ov, ss = ma.read_result(res)
     assert not ov and abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref
     assert np.float32(ma.clip_coef(ss, 1.0)) == c_ref
-    assert_state_close(_sample_state(fl, ranges, "bf16"), before, "8B list sample")
+    assert_state_close(_sample_list(ls, per, "bf16"), before, "8B list sample (%s)" % layout)
     # one NaN in a norm vector: the whole list is skipped, checked over every byte via checksums
-    sums = _checksums(fl)
+    sums = _checksums_list(ls)
     ls.g[8].view(torch.int16)[4095] = 0x7FC0
     ma.multi_overflow_norm(plan, 1.0, res, ws)
     ma.multi_adamw_step_gated(plan, _hyper(cfg), 101, 1.0, res, 1.0)
     assert ma.read_result(res)[0] is True
-    assert _checksums(fl) == sums
+    assert _checksums_list(ls) == sums
 
 
 def test_14b_class_four_sub_groups_sampled():

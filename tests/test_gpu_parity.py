@@ -283,13 +283,13 @@ def test_fp32_gradients():
     assert ma.read_result(res, 1)[0] is True
 
 
-@pytest.mark.parametrize("align_elems", [64, 1])
-def test_multi_tensor_list_miniature(align_elems):
+@pytest.mark.parametrize("align_elems,layout", [(64, "streams"), (1, "streams"), (64, "tensor")])
+def test_multi_tensor_list_miniature(align_elems, layout):
     """A 1/4096-scale Llama-3-8B-shaped list (290 tensors, ragged sizes): one scan launch, one
     gated update launch, compared tensor by tensor with the oracle run on the same list."""
     shapes = synth.scaled_shapes(synth.llama3_8b_shapes(), 4096, ragged=True)
     cfg = synth.FlatConfig("t", 0, seed=51, m_std=1e-4, v_std=1e-8, step=100, max_norm=0.05)
-    ls = synth.make_list(shapes, cfg, device="cuda", align_elems=align_elems)
+    ls = synth.make_list(shapes, cfg, device="cuda", align_elems=align_elems, layout=layout)
     refs, g_hosts = [], []
     for i in range(len(shapes)):
         refs.append(dict(p=host_f32(ls.p[i]), m=host_f32(ls.m[i]), v=host_f32(ls.v[i]),
@@ -317,13 +317,14 @@ def test_multi_tensor_list_miniature(align_elems):
     for i in range(len(shapes)):
         got = dict(p=host_f32(ls.p[i]), m=host_f32(ls.m[i]), v=host_f32(ls.v[i]), lp=synth.bits16(ls.p_lp[i]))
         assert_state_close(got, refs[i], "tensor %d (%s)" % (i, shapes[i][0]))
-    # overflow in one small tensor gates the whole list
-    before = host_f32(ls.flat.p)
+    # overflow in one small tensor gates the whole list: not one byte of the allocation changes
     ls.g[7].view(torch.int16)[0] = 0x7FC0
+    whole = ls.flat.arena if layout == "streams" else ls.arena
+    before = whole.cpu().numpy().tobytes()
     ma.multi_overflow_norm(plan, 1.0, res, ws)
     ma.multi_adamw_step_gated(plan, _hyper(cfg), 101, 1.0, res, cfg.max_norm)
     assert ma.read_result(res)[0] is True
-    assert host_f32(ls.flat.p).tobytes() == before.tobytes()
+    assert whole.cpu().numpy().tobytes() == before
 
 
 def test_multi_ungated_equals_gated_with_same_clip():
