@@ -12,7 +12,10 @@ bounded sample of the same workload.
 
 Workloads: llama3_8b (default; 290-tensor Llama-3-8B-shaped list, 8.03e9 elements, bf16
 gradients, clip 1.0; --layout tensor|streams), flat_1e8, fp16_5e7, c1, qwen14b_4sub (12.57e9 elements as 4 flat
-sub-groups streamed on one stream).
+sub-groups streamed on one stream); rows beyond the basic step at the 8B element count:
+bf16_states_8b (p/m/v held in bf16, truncating stores, 14 B/param), accumulate_8b (4 bf16
+micro-batch gradients into the fp32 flat buffer, 6 / 10 B/param), auto_fp16_8b (fp16 gradients,
+loss scale, update number and gate all read on the device).
 """
 import argparse
 import json
@@ -73,13 +76,21 @@ class Workload:
         # placement "region": the state is cut from one whole-device allocation at the offset
         # that splits its traffic evenly over two of the three 96 GiB HBM regions (hbm.py);
         # "plain": a fresh allocation of just the state's size, wherever the driver puts it
-        self.device_arena = hbm.DeviceArena("cuda") if placement == "region" else None
+        self.device_arena = None
+        if placement == "region":
+            try:
+                self.device_arena = hbm.DeviceArena("cuda")
+            except RuntimeError as e:      # e.g. another process holds most of the device
+                log("bench.py: whole-device arena not available (%s); falling back to a plain allocation" % e)
+                self.placement = placement = "plain"
         place = (lambda nbytes, traffic: self.device_arena.window(nbytes, traffic)) \
             if self.device_arena else (lambda nbytes, traffic: None)
         self.ws = ma.workspace()
         self.res = ma.new_result()
         self.t = 100
         self.events = []
+        self.step_bytes = STEP_BYTES_PER_PARAM
+        self.kernel_label = "AdamW update (+ low-precision copy)"
         if name == "llama3_8b":
             cfg = synth.FlatConfig(name, 0, seed=3, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
             self.cfg = cfg
@@ -105,6 +116,57 @@ class Workload:
             self.parts = ma.new_result(4)
             self.desc = ("14B-class list (%d elements) as 4 equal flat sub-groups streamed on one "
                          "stream, bf16 grads, clip 1.0" % total)
+        elif name in ("bf16_states_8b", "accumulate_8b"):
+            # flat sub-groups of the 8B element count for the rows beyond the basic step
+            n = sum(k for _, k in synth.llama3_8b_shapes())
+            cfg = synth.FlatConfig(name, n, seed=5, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
+            self.cfg, self.n = cfg, n
+            up = lambda x: (x + synth.ARENA_ALIGN - 1) // synth.ARENA_ALIGN * synth.ARENA_ALIGN
+            if name == "bf16_states_8b":
+                sizes, weights = [up(2 * n)] * 4, (2.0, 2.0, 2.0, 1.0)
+                self.step_bytes, self.kind = 14.0, "bf16"
+                self.kernel_label = "AdamW update, bf16 p/m/v stored by truncation"
+                self.desc = "flat sub-group n=%d, bf16 p/m/v (truncating stores), bf16 grads, clip 1.0" % n
+            else:
+                sizes, weights = [up(4 * n), up(2 * n)], (2.0, 1.0)
+                self.step_bytes, self.kind = 10.0, "accum"
+                self.micro = 4
+                self.kernel_label = "gradient accumulation into the fp32 flat buffer (2nd and later micro-batches)"
+                self.desc = ("fp32 flat gradient buffer n=%d, %d bf16 micro-batch gradients per step "
+                             "(first overwrites, the others add)" % (n, self.micro))
+            buf = place(sum(sizes), list(zip(sizes, weights)))
+            if buf is None:
+                buf = torch.empty(sum(sizes), dtype=torch.uint8, device="cuda")
+            self.raw = buf
+            offs = [sum(sizes[:i]) for i in range(len(sizes))]
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(cfg.seed)
+            if name == "bf16_states_8b":
+                self.bp, self.bm, self.bv, self.bg = (buf[o:o + 2 * n].view(torch.bfloat16) for o in offs)
+                for t, std in ((self.bp, cfg.p_std), (self.bm, cfg.m_std), (self.bv, cfg.v_std), (self.bg, cfg.g_std)):
+                    synth._fill_grad(t, std, 1.0, gen)
+                self.bv.abs_()
+            else:
+                self.acc = buf[offs[0]:offs[0] + 4 * n].view(torch.float32)
+                self.bg = buf[offs[1]:offs[1] + 2 * n].view(torch.bfloat16)
+                synth._fill_grad(self.bg, cfg.g_std, 1.0, gen)
+        elif name == "auto_fp16_8b":
+            cfg = synth.FlatConfig(name, 0, seed=7, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0,
+                                   gdt="f16", loss_scale=65536.0)
+            self.cfg = cfg
+            self.layout = layout
+            shapes = synth.llama3_8b_shapes()
+            self.state = synth.make_list(shapes, cfg, device="cuda", layout=layout,
+                                         arena=place(synth.list_state_bytes(shapes, layout),
+                                                     synth.list_traffic(shapes, layout)))
+            self.plan = ma.MultiPlan(self.state.p, self.state.m, self.state.v, self.state.g,
+                                     self.state.p_lp)
+            self.n = self.plan.total
+            self.kind = "auto"
+            self.scaler = ma.new_scaler(cfg.loss_scale, 99)
+            self.scaler_cfg = ma.scaler_config(window=1000)
+            self.desc = ("8B-shaped list, fp16 grads at loss scale 65536 kept on the device: scan, gated "
+                         "update and loss-scale update without host round trip; layout '%s'" % layout)
         else:
             cfg = synth.config({"flat_1e8": "c2", "fp16_5e7": "c3a", "c1": "c1"}[name])
             self.cfg = cfg
@@ -128,6 +190,24 @@ class Workload:
             if record:
                 ev[1].record()
             ma.multi_adamw_step_gated(self.plan, self.h, self.t, c.loss_scale, self.res, c.max_norm)
+        elif self.kind == "auto":
+            ma.multi_overflow_norm_auto(self.plan, self.scaler, self.res, self.ws)
+            if record:
+                ev[1].record()
+            ma.multi_adamw_step_auto(self.plan, self.h, self.scaler, self.res, c.max_norm)
+            ma.scaler_update(self.scaler, self.res, self.scaler_cfg)
+        elif self.kind == "bf16":
+            ma.overflow_norm(self.bg, c.loss_scale, self.res, self.ws)
+            if record:
+                ev[1].record()
+            ma.adamw_step_bf16_gated(self.bp, self.bm, self.bv, self.bg, self.h, self.t, c.loss_scale,
+                                     self.res, c.max_norm)
+        elif self.kind == "accum":
+            ma.grad_accumulate(self.acc, self.bg, first=True)
+            if record:
+                ev[1].record()
+            for _ in range(self.micro - 1):
+                ma.grad_accumulate(self.acc, self.bg, first=False)
         elif self.kind == "flat":
             f = self.flat
             ma.overflow_norm(f.g, c.loss_scale, self.res, self.ws)
@@ -199,7 +279,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama3_8b",
-                    choices=["llama3_8b", "flat_1e8", "fp16_5e7", "c1", "qwen14b_4sub"])
+                    choices=["llama3_8b", "flat_1e8", "fp16_5e7", "c1", "qwen14b_4sub",
+                             "bf16_states_8b", "accumulate_8b", "auto_fp16_8b"])
     ap.add_argument("--layout", default="streams", choices=["streams", "tensor"],
                     help="llama3_8b only: how the list's buffers lie in the state: 'streams' = five flat "
                          "buffers p|m|v|g|p_lp (default), 'tensor' = the five buffers of each tensor adjacent")
@@ -240,7 +321,9 @@ def main():
     if args.copy_calibration > 0:
         nb = args.copy_calibration
         if wl.device_arena is not None:      # the arena holds the device's memory: use its unused tail
-            buf, state = wl.device_arena.buf, (wl.state.arena if wl.kind == "multi" else wl.flat.arena)
+            buf = wl.device_arena.buf
+            state = (wl.state.arena if wl.kind in ("multi", "auto") else
+                     wl.raw if wl.kind in ("bf16", "accum") else wl.flat.arena)
             tail = buf.numel() - (state.data_ptr() - buf.data_ptr() + state.numel())
             if tail < 2 * nb:
                 sys.exit("bench.py: --copy-calibration needs %d free bytes behind the state" % (2 * nb))
@@ -254,18 +337,34 @@ def main():
         torch.cuda.synchronize()
         log("copy calibration: %d bytes read, %d bytes written" % (src.numel(), dst.numel()))
         del src, dst
-    scan_ms = sum(e[0].elapsed_time(e[1]) for e in wl.events) / len(wl.events)
-    upd_ms = sum(e[1].elapsed_time(e[2]) for e in wl.events) / len(wl.events)
-    launches = 4 if wl.kind == "sub" else 1      # update launches per step
-    log("update ms per step: " + " ".join("%.3f" % e[1].elapsed_time(e[2]) for e in wl.events))
-    log("scan   ms per step: " + " ".join("%.3f" % e[0].elapsed_time(e[1]) for e in wl.events))
-    ov, ss = ma.read_result(wl.res)
-    if ov:
-        sys.exit("bench.py: unexpected overflow flag on clean synthetic gradients")
-    achieved = STEP_BYTES_PER_PARAM * wl.n / (upd_ms * 1e-3) / 1e9
+    first_ms = sum(e[0].elapsed_time(e[1]) for e in wl.events) / len(wl.events)
+    rest_ms = sum(e[1].elapsed_time(e[2]) for e in wl.events) / len(wl.events)
+    log("2nd phase ms per step: " + " ".join("%.3f" % e[1].elapsed_time(e[2]) for e in wl.events))
+    log("1st phase ms per step: " + " ".join("%.3f" % e[0].elapsed_time(e[1]) for e in wl.events))
+    if wl.kind != "accum":
+        ov, ss = ma.read_result(wl.res)
+        if ov:
+            sys.exit("bench.py: unexpected overflow flag on clean synthetic gradients")
+    else:
+        ss = None
+    # launches of the dominant kernel in the second phase of a step, and what precedes them
+    launches = {"sub": 4, "accum": wl.micro - 1 if wl.kind == "accum" else 1}.get(wl.kind, 1)
+    passes = launches if wl.kind == "accum" else 1          # times the second phase sweeps all n elements
+    achieved = wl.step_bytes * wl.n * passes / (rest_ms * 1e-3) / 1e9
+    gdt_bytes = 2.0
+    if wl.kind == "accum":
+        first = {"kernel": "first micro-batch (overwrite)", "avg_ms": first_ms, "bytes_per_param": 6.0,
+                 "achieved": 6.0 * wl.n / (first_ms * 1e-3) / 1e9}
+        value = wl.n * wl.micro / (ms_per_step * 1e-3) / 1e9       # micro-batch elements accumulated
+        whole = (6.0 + 10.0 * (wl.micro - 1)) * wl.n / (ms_per_step * 1e-3) / 1e9
+    else:
+        first = {"kernel": "gradient scan (+ finalize)", "avg_ms": first_ms, "bytes_per_param": gdt_bytes,
+                 "achieved": gdt_bytes * wl.n / (first_ms * 1e-3) / 1e9}
+        value = wl.n / (ms_per_step * 1e-3) / 1e9
+        whole = (gdt_bytes + wl.step_bytes) * wl.n / (ms_per_step * 1e-3) / 1e9
     out = {
         "metric": "optimizer-step Gparam/s and achieved HBM GB/s (% of peak), 8B-shaped, 1 GPU",
-        "value": wl.n / (ms_per_step * 1e-3) / 1e9,
+        "value": value,
         "unit": "Gparam/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
@@ -277,18 +376,18 @@ def main():
                    "max_norm": wl.cfg.max_norm, "loss_scale": wl.cfg.loss_scale,
                    "sumsq_last_step": ss},
         "roofline": {
-            "bound": "hbm", "kernel": "AdamW update (+ low-precision copy)",
+            "bound": "hbm", "kernel": wl.kernel_label,
             "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
-            "algorithmic_bytes_per_launch": STEP_BYTES_PER_PARAM * wl.n / launches,
-            "bytes_per_param": STEP_BYTES_PER_PARAM, "params_per_launch": wl.n / launches,
-            "avg_launch_ms": upd_ms / launches,
-            "scan": {"avg_ms": scan_ms, "bytes_per_param": SCAN_BYTES_PER_PARAM,
-                     "achieved": SCAN_BYTES_PER_PARAM * wl.n / (scan_ms * 1e-3) / 1e9},
-            "whole_step_GBps": 30.0 * wl.n / (ms_per_step * 1e-3) / 1e9,
+            "algorithmic_bytes_per_launch": wl.step_bytes * wl.n / (4 if wl.kind == "sub" else 1),
+            "bytes_per_param": wl.step_bytes,
+            "params_per_launch": wl.n / (4 if wl.kind == "sub" else 1),
+            "avg_launch_ms": rest_ms / launches,
+            "first_phase": first,
+            "whole_step_GBps": whole,
         },
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and wl.kind in ("multi", "flat", "sub"):
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample, args.cpu_passes)
     print(json.dumps(out), flush=True)
 

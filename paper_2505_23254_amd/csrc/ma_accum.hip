@@ -3,21 +3,33 @@
 //
 // acc[i] = first ? widen(g[i]) : acc[i] + widen(g[i])  -- one fp32 addition per element.
 // HBM-bound: 2 B read + 4 B written per element for the first micro-batch of an iteration,
-// 2 + 4 read and 4 written afterwards (16-bit gradients).  Same packets, hints and persistent
-// grid as the update kernel.
+// 2 + 4 read and 4 written afterwards (16-bit gradients).  Same packets and hints as the update
+// kernel; a persistent grid of one block per CU with the XCD-contiguous work assignment, which
+// keeps the eight XCDs at eight different places of the two buffers (with all blocks sweeping one
+// moving window the kernel was 25 % slower whenever both buffers lay in the same region of HBM).
+// Measured best depth: eight groups per lane in flight for the overwrite, four for the add.
 
 #include "ma_internal.h"
 
-#ifndef MA_ACCUM_UNROLL
-#define MA_ACCUM_UNROLL 4
+#ifndef MA_ACCUM_UNROLL_FIRST
+#define MA_ACCUM_UNROLL_FIRST 8  // 4-element groups per lane and work item, overwrite
+#endif
+#ifndef MA_ACCUM_UNROLL_ADD
+#define MA_ACCUM_UNROLL_ADD 4  // the same, add
 #endif
 #ifndef MA_ACCUM_BLOCKS_PER_CU
-#define MA_ACCUM_BLOCKS_PER_CU 2
+#define MA_ACCUM_BLOCKS_PER_CU 1
+#endif
+#ifndef MA_ACCUM_MAP
+#define MA_ACCUM_MAP 2  // work-item assignment (see WorkIter)
 #endif
 
 namespace ma {
 
-constexpr int kAccumUnroll = MA_ACCUM_UNROLL;
+template <bool FIRST>
+constexpr int accum_unroll() {
+  return FIRST ? MA_ACCUM_UNROLL_FIRST : MA_ACCUM_UNROLL_ADD;
+}
 
 template <int GDT>
 __device__ __forceinline__ float accum_grad1(MA_GLOBAL const char* g, uint64_t i) {
@@ -53,6 +65,7 @@ __global__ __launch_bounds__(kBlock) void accumulate_kernel(float* acc_, const v
                                                            uint32_t head, uint32_t vec,
                                                            uint64_t chunks) {
   using GPacket = typename std::conditional<GDT == kF32, f32x4, u32x2>::type;
+  constexpr int kAccumUnroll = accum_unroll<FIRST>();
   constexpr uint64_t kChunkGroups = uint64_t(kBlock) * kAccumUnroll;
   MA_GLOBAL float* acc = to_global(acc_);
   MA_GLOBAL const char* g = to_global(static_cast<const char*>(g_));
@@ -73,7 +86,7 @@ __global__ __launch_bounds__(kBlock) void accumulate_kernel(float* acc_, const v
     const uint64_t t0 = uint64_t(head) + ngroups * 4;
     if (n > head && t0 + tid < n) accum1<GDT, FIRST>(acc, g, t0 + tid);
   }
-  for (WorkIter<0> w(chunks); w.c < w.end; w.c += w.stride) {
+  for (WorkIter<MA_ACCUM_MAP> w(chunks); w.c < w.end; w.c += w.stride) {
     const uint64_t g0 = w.c * kChunkGroups + tid;
     if ((w.c + 1) * kChunkGroups <= ngroups) {
       GPacket G[kAccumUnroll];
@@ -120,7 +133,7 @@ static hipError_t launch_accumulate_g(float* acc, const void* g, uint64_t n, uin
 hipError_t launch_accumulate(float* acc, const void* g, int gdt, uint64_t n, uint32_t head,
                              uint32_t vec, int first, int device_cus, hipStream_t stream) {
   if (n == 0) return hipSuccess;
-  constexpr uint64_t kChunkElems = uint64_t(kBlock) * 4 * kAccumUnroll;
+  const uint64_t kChunkElems = uint64_t(kBlock) * 4 * (first ? accum_unroll<true>() : accum_unroll<false>());
   const uint64_t body = (vec && n > head) ? n - head : 0;
   const uint64_t chunks = vec ? (body + kChunkElems - 1) / kChunkElems : 0;
   const uint64_t want = uint64_t(device_cus) * MA_ACCUM_BLOCKS_PER_CU;

@@ -3,34 +3,42 @@
 // parameters).
 //
 // HBM-bound: per element the kernel reads p, m, v (fp32) and the gradient (16-bit), and writes
-// p, m, v and the 16-bit parameter copy: 14 + 14 = 28 bytes, about 45 ALU instructions.  Each
-// lane owns groups of four consecutive elements, so p/m/v move as 128-bit packets and the
-// 16-bit operands as 64-bit packets; a wave covers 1 KiB (512 B) of contiguous memory per
-// instruction.  The arithmetic runs in registers and every packet carries the non-temporal hint
-// since nothing is read again.  Work items are handed to a persistent, fully resident grid sized
-// to the CU count (WorkIter), and each wave keeps the loads of its next work item in flight while
-// it finishes the current one.
+// p, m, v and the 16-bit parameter copy: 14 + 14 = 28 bytes, about 55 ALU instructions.  Each
+// lane owns groups of consecutive elements sized so that p, m, v move as 128-bit packets (four
+// fp32 elements; the 16-bit operands of such a group are 64-bit packets).  The arithmetic runs in
+// registers and every packet carries the non-temporal hint since nothing is read again.  Work
+// items are handed to a persistent, fully resident grid sized to the CU count (WorkIter), and
+// each wave keeps the loads of its next work item in flight while it finishes the current one.
 //
 // The same code also serves optimizer states held in bf16 and stored by truncation (Extended
-// Experiments, bf16 half-precision optimizer): only the packets and their pack/unpack differ.
+// Experiments, bf16 half-precision optimizer): a group is then eight elements, again one 128-bit
+// packet per state stream, widened by a shift and stored back by dropping the low half.
 
 #include "ma_internal.h"
 
 namespace ma {
 
-// ---- operand packets: four consecutive elements of one stream ---------------------------------------
+// ---- operand packets: one group of consecutive elements of one stream -------------------------------
 
-template <int GDT>
+// Gradient of a group of GROUP elements: one packet of 16-bit values, or GROUP/4 fp32 packets.
+template <int GDT, int GROUP>
 struct GradGroup {
-  using Packet = typename std::conditional<GDT == kF32, f32x4, u32x2>::type;
-  Packet raw;
+  static constexpr int kPackets = (GDT == kF32) ? GROUP / 4 : 1;
+  using Packet = typename std::conditional<
+      GDT == kF32, f32x4, typename std::conditional<GROUP == 4, u32x2, u32x4>::type>::type;
+  Packet raw[kPackets];
   __device__ __forceinline__ float get(int k) const {
     if constexpr (GDT == kF32) {
-      return raw[k];
+      return raw[k >> 2][k & 3];
     } else {
-      const uint32_t w = raw[k >> 1];
+      const uint32_t w = raw[0][k >> 1];
       return widen16<GDT>((k & 1) ? (w >> 16) : (w & 0xFFFFu));
     }
+  }
+  // base points at the row's first whole group
+  __device__ __forceinline__ void load(MA_GLOBAL const Packet* base, uint64_t gi) {
+#pragma unroll
+    for (int j = 0; j < kPackets; ++j) raw[j] = ld_stream(base + gi * kPackets + j);
   }
 };
 
@@ -43,33 +51,37 @@ __device__ __forceinline__ uint32_t truncate_bf16(float x) {
   return h;
 }
 
-// State streams (p, m, v): fp32, or bf16 widened on load and truncated on store.
+// State streams (p, m, v): fp32, or bf16 widened on load and truncated on store.  One packet is
+// 16 bytes = one group.
 template <int SDT>
 struct StateIO {
-  using Packet = typename std::conditional<SDT == kF32, f32x4, u32x2>::type;
+  static constexpr int kGroup = step_group_elems(SDT);
+  static constexpr int kUnroll = step_unroll(SDT);
   static constexpr uint64_t kBytes = (SDT == kF32) ? 4 : 2;
+  using Packet = typename std::conditional<SDT == kF32, f32x4, u32x4>::type;
 
-  static __device__ __forceinline__ f32x4 unpack(Packet r) {
+  static __device__ __forceinline__ void unpack(Packet r, float (&x)[kGroup]) {
     if constexpr (SDT == kF32) {
-      return r;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) x[k] = r[k];
     } else {
-      f32x4 x;
-      x[0] = bits_to_f32(r.x << 16);
-      x[1] = bits_to_f32(r.x & 0xFFFF0000u);
-      x[2] = bits_to_f32(r.y << 16);
-      x[3] = bits_to_f32(r.y & 0xFFFF0000u);
-      return x;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        x[2 * k] = bits_to_f32(r[k] << 16);
+        x[2 * k + 1] = bits_to_f32(r[k] & 0xFFFF0000u);
+      }
     }
   }
-  static __device__ __forceinline__ Packet pack(f32x4 x) {
+  static __device__ __forceinline__ Packet pack(const float (&x)[kGroup]) {
+    Packet r;
     if constexpr (SDT == kF32) {
-      return x;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) r[k] = x[k];
     } else {
-      Packet r;
-      r.x = truncate_bf16(x[0]) | (truncate_bf16(x[1]) << 16);
-      r.y = truncate_bf16(x[2]) | (truncate_bf16(x[3]) << 16);
-      return r;
+#pragma unroll
+      for (int k = 0; k < 4; ++k) r[k] = truncate_bf16(x[2 * k]) | (truncate_bf16(x[2 * k + 1]) << 16);
     }
+    return r;
   }
   static __device__ __forceinline__ float load1(MA_GLOBAL const char* base, uint64_t i) {
     if constexpr (SDT == kF32) {
@@ -123,23 +135,23 @@ __device__ __forceinline__ void step_scalar_element(const StepScalars& s, const 
   store_lp_scalar<PDT>(r.lp, i, pi);
 }
 
-// Four elements: unpack, update, pack.  L receives the 16-bit parameter copy.
+// One group: unpack, update, pack.  L receives the 16-bit parameter copy (fp32 states only, where a
+// group is four elements).
 template <int SDT, int GDT, int PDT>
 __device__ __forceinline__ void step_group(const StepScalars& s, typename StateIO<SDT>::Packet& Pr,
                                            typename StateIO<SDT>::Packet& Mr,
-                                           typename StateIO<SDT>::Packet& Vr, const GradGroup<GDT>& G,
-                                           u32x2& L) {
+                                           typename StateIO<SDT>::Packet& Vr,
+                                           const GradGroup<GDT, StateIO<SDT>::kGroup>& G, u32x2& L) {
   using S = StateIO<SDT>;
-  f32x4 P = S::unpack(Pr), M = S::unpack(Mr), V = S::unpack(Vr);
+  constexpr int N = S::kGroup;
+  float P[N], M[N], V[N];
+  S::unpack(Pr, P);
+  S::unpack(Mr, M);
+  S::unpack(Vr, V);
 #pragma unroll
-  for (int k = 0; k < 4; ++k) {
-    float pk = P[k], mk = M[k], vk = V[k];
-    adamw_element(s, G.get(k), pk, mk, vk);
-    P[k] = pk;
-    M[k] = mk;
-    V[k] = vk;
-  }
+  for (int k = 0; k < N; ++k) adamw_element(s, G.get(k), P[k], M[k], V[k]);
   if constexpr (PDT != kNoLp) {
+    static_assert(N == 4, "the 16-bit parameter copy exists for fp32 states only");
     L.x = narrow16<PDT>(P[0]) | (narrow16<PDT>(P[1]) << 16);
     L.y = narrow16<PDT>(P[2]) | (narrow16<PDT>(P[3]) << 16);
   }
@@ -170,11 +182,11 @@ __device__ __forceinline__ RowPtrs row_ptrs(const Item& it) {
   return r;
 }
 
-// Packet pointers of the row's 4-element-group-aligned body.
+// Packet pointers of the row's group-aligned body.
 template <int SDT, int GDT>
 struct BodyPtrs {
   using SPacket = typename StateIO<SDT>::Packet;
-  using GPacket = typename GradGroup<GDT>::Packet;
+  using GPacket = typename GradGroup<GDT, StateIO<SDT>::kGroup>::Packet;
   MA_GLOBAL SPacket* p;
   MA_GLOBAL SPacket* m;
   MA_GLOBAL SPacket* v;
@@ -191,19 +203,22 @@ struct BodyPtrs {
 };
 
 // ---- the general work item (ragged, head-carrying or misaligned) --------------------------------------
-// kStepChunkElems elements of the group-aligned body; item 0 also takes the head elements, the
-// last item the ragged tail.  Rows whose buffers cannot be brought to a common group alignment run
-// the scalar loop.
+// step_chunk_elems(SDT) elements of the group-aligned body; item 0 also takes the head elements,
+// the last item the ragged tail.  Rows whose buffers cannot be brought to a common group alignment
+// run the scalar loop.
 template <int SDT, int GDT, int PDT>
 __device__ __forceinline__ void step_chunk(const StepScalars& s, const Item& it) {
+  using S = StateIO<SDT>;
+  constexpr uint64_t kChunkElems = step_chunk_elems(SDT);
+  constexpr uint64_t kChunkGroups = uint64_t(kBlock) * S::kUnroll;
   const uint32_t tid = threadIdx.x;
   const RowPtrs r = row_ptrs(it);
   const uint64_t n = it.n, lc = it.lc;
   const uint32_t head = it.head;
 
   if (!it.vec) {
-    const uint64_t e0 = lc * kStepChunkElems;
-    const uint64_t e1 = (n - e0 < kStepChunkElems) ? n : e0 + kStepChunkElems;
+    const uint64_t e0 = lc * kChunkElems;
+    const uint64_t e1 = (n - e0 < kChunkElems) ? n : e0 + kChunkElems;
     for (uint64_t i = e0 + tid; i < e1; i += kBlock) step_scalar_element<SDT, GDT, PDT>(s, r, i);
     return;
   }
@@ -211,18 +226,17 @@ __device__ __forceinline__ void step_chunk(const StepScalars& s, const Item& it)
   if (lc == 0 && tid < head && tid < n) step_scalar_element<SDT, GDT, PDT>(s, r, tid);
   if (n <= head) return;
 
-  constexpr uint64_t kChunkGroups = uint64_t(kBlock) * kStepUnroll;
-  const uint64_t ngroups = (n - head) / 4;
+  const uint64_t ngroups = (n - head) / S::kGroup;
   const uint64_t g0 = lc * kChunkGroups;
   const BodyPtrs<SDT, GDT> b(r, head);
 
 #pragma unroll
-  for (int u = 0; u < kStepUnroll; ++u) {
+  for (int u = 0; u < S::kUnroll; ++u) {
     const uint64_t gi = g0 + tid + uint64_t(u) * kBlock;
     if (gi < ngroups) {
-      typename StateIO<SDT>::Packet P = ld_stream(b.p + gi), M = ld_stream(b.m + gi), V = ld_stream(b.v + gi);
-      GradGroup<GDT> G;
-      G.raw = ld_stream(b.g + gi);
+      typename S::Packet P = ld_stream(b.p + gi), M = ld_stream(b.m + gi), V = ld_stream(b.v + gi);
+      GradGroup<GDT, S::kGroup> G;
+      G.load(b.g, gi);
       u32x2 L;
       step_group<SDT, GDT, PDT>(s, P, M, V, G, L);
       st_stream(b.p + gi, P);
@@ -231,8 +245,8 @@ __device__ __forceinline__ void step_chunk(const StepScalars& s, const Item& it)
       if constexpr (PDT != kNoLp) st_stream(b.lp + gi, L);
     }
   }
-  // fewer than four elements remain after the row's last group; they belong to its last item
-  const uint64_t t0 = uint64_t(head) + ngroups * 4;
+  // fewer than one group's elements remain after the row's last group; they belong to its last item
+  const uint64_t t0 = uint64_t(head) + ngroups * S::kGroup;
   if (g0 + kChunkGroups > ngroups && t0 + tid < n) step_scalar_element<SDT, GDT, PDT>(s, r, t0 + tid);
 }
 
@@ -244,28 +258,31 @@ __device__ __forceinline__ void step_chunk(const StepScalars& s, const Item& it)
 
 // Whole, aligned work items take the tile path; a row's first item when it has head elements,
 // its ragged last item, and every item of a misaligned row go through step_chunk.
+template <int SDT>
 __device__ __forceinline__ bool item_is_tile(const Item& it) {
-  constexpr uint64_t kChunkGroups = uint64_t(kBlock) * kStepUnroll;
+  constexpr uint64_t kChunkGroups = uint64_t(kBlock) * StateIO<SDT>::kUnroll;
   if (!it.vec || it.n <= it.head) return false;
   if (it.lc == 0 && it.head != 0) return false;
-  return (it.lc + 1) * kChunkGroups <= (it.n - it.head) / 4;
+  return (it.lc + 1) * kChunkGroups <= (it.n - it.head) / StateIO<SDT>::kGroup;
 }
 
 template <int SDT, int GDT>
 struct Tile {
-  typename StateIO<SDT>::Packet P[kStepUnroll], M[kStepUnroll], V[kStepUnroll];
-  GradGroup<GDT> G[kStepUnroll];
+  static constexpr int kUnroll = StateIO<SDT>::kUnroll;
+  typename StateIO<SDT>::Packet P[kUnroll], M[kUnroll], V[kUnroll];
+  GradGroup<GDT, StateIO<SDT>::kGroup> G[kUnroll];
 };
 
 template <int SDT, int GDT>
 __device__ __forceinline__ void tile_load(Tile<SDT, GDT>& t, const Item& it) {
-  constexpr uint64_t kChunkGroups = uint64_t(kBlock) * kStepUnroll;
+  constexpr int kUnroll = StateIO<SDT>::kUnroll;
+  constexpr uint64_t kChunkGroups = uint64_t(kBlock) * kUnroll;
   const uint64_t g0 = it.lc * kChunkGroups + threadIdx.x;
   const BodyPtrs<SDT, GDT> b(row_ptrs(it), it.head);
 #pragma unroll
-  for (int u = 0; u < kStepUnroll; ++u) {
+  for (int u = 0; u < kUnroll; ++u) {
     const uint64_t gi = g0 + uint64_t(u) * kBlock;
-    t.G[u].raw = ld_stream(b.g + gi);
+    t.G[u].load(b.g, gi);
     t.P[u] = ld_stream(b.p + gi);
     t.M[u] = ld_stream(b.m + gi);
     t.V[u] = ld_stream(b.v + gi);
@@ -274,14 +291,15 @@ __device__ __forceinline__ void tile_load(Tile<SDT, GDT>& t, const Item& it) {
 
 template <int SDT, int GDT, int PDT>
 __device__ __forceinline__ void tile_finish(Tile<SDT, GDT>& t, const Item& it, const StepScalars& s) {
-  constexpr uint64_t kChunkGroups = uint64_t(kBlock) * kStepUnroll;
+  constexpr int kUnroll = StateIO<SDT>::kUnroll;
+  constexpr uint64_t kChunkGroups = uint64_t(kBlock) * kUnroll;
   const uint64_t g0 = it.lc * kChunkGroups + threadIdx.x;
   const BodyPtrs<SDT, GDT> b(row_ptrs(it), it.head);
-  u32x2 L[kStepUnroll];
+  u32x2 L[kUnroll];
 #pragma unroll
-  for (int u = 0; u < kStepUnroll; ++u) step_group<SDT, GDT, PDT>(s, t.P[u], t.M[u], t.V[u], t.G[u], L[u]);
+  for (int u = 0; u < kUnroll; ++u) step_group<SDT, GDT, PDT>(s, t.P[u], t.M[u], t.V[u], t.G[u], L[u]);
 #pragma unroll
-  for (int u = 0; u < kStepUnroll; ++u) {
+  for (int u = 0; u < kUnroll; ++u) {
     const uint64_t gi = g0 + uint64_t(u) * kBlock;
     st_stream(b.p + gi, t.P[u]);
     st_stream(b.m + gi, t.M[u]);
@@ -316,7 +334,7 @@ __device__ __forceinline__ void step_pipeline(const StepScalars& s, uint64_t chu
   Item ia, ib;
   Tile<SDT, GDT> ta, tb;
   locate(w.c, ia);
-  bool fa = item_is_tile(ia), fb = false;
+  bool fa = item_is_tile<SDT>(ia), fb = false;
   if (fa) tile_load<SDT, GDT>(ta, ia);
   for (;;) {
     // A is current; start B
@@ -324,7 +342,7 @@ __device__ __forceinline__ void step_pipeline(const StepScalars& s, uint64_t chu
     bool more = next < w.end;
     if (more) {
       locate(next, ib);
-      fb = item_is_tile(ib);
+      fb = item_is_tile<SDT>(ib);
       if (fb) tile_load<SDT, GDT>(tb, ib);
     }
     item_finish<SDT, GDT, PDT>(fa, ta, ia, s);
@@ -335,7 +353,7 @@ __device__ __forceinline__ void step_pipeline(const StepScalars& s, uint64_t chu
     more = next < w.end;
     if (more) {
       locate(next, ia);
-      fa = item_is_tile(ia);
+      fa = item_is_tile<SDT>(ia);
       if (fa) tile_load<SDT, GDT>(ta, ia);
     }
     item_finish<SDT, GDT, PDT>(fb, tb, ib, s);
@@ -448,7 +466,11 @@ static hipError_t launch_step_typed(const Desc* row_host, const Desc* table_dev,
   static const int occ_flat = resident_blocks_per_cu(step_flat_kernel<SDT, GDT, PDT>);
   static const int occ_multi = resident_blocks_per_cu(step_multi_kernel<SDT, GDT, PDT>);
   const int occ = row_host ? occ_flat : occ_multi;
-  const uint64_t want = uint64_t(device_cus) * (occ < MA_STEP_BLOCKS_PER_CU ? occ : MA_STEP_BLOCKS_PER_CU);
+  // fp32 states: one block per CU (the 1:1 read/write mix is fastest with few, deep waves);
+  // bf16 states move half the bytes per element, so arithmetic and memory time are comparable and a
+  // second block per CU overlaps the two
+  constexpr int kPerCu = (SDT == kF32) ? MA_STEP_BLOCKS_PER_CU : MA_STEP_BLOCKS_PER_CU_BF16;
+  const uint64_t want = uint64_t(device_cus) * (occ < kPerCu ? occ : kPerCu);
   const uint32_t grid = static_cast<uint32_t>(chunks < want ? chunks : want);
   if (row_host) {
     step_flat_kernel<SDT, GDT, PDT><<<grid, kBlock, 0, stream>>>(*row_host, chunks, s, ctl);

@@ -116,20 +116,25 @@ int plan_row(ma::Desc& d, int gdt, bool has_lp, uint64_t* norm_chunks, uint64_t*
   if (!aligned(d.p, sb) || !aligned(d.m, sb) || !aligned(d.v, sb))
     return fail(MA_ERR_ALIGN, "p/m/v pointers must be aligned to their element size");
   if (has_lp && !aligned(d.lp, 2)) return fail(MA_ERR_ALIGN, "p_lp pointer must be 2-byte aligned");
-  // update: a head of h elements must bring all five buffers to a 4-element-group boundary
-  const uint32_t h =
-      uint32_t(((4 * sb - (reinterpret_cast<uintptr_t>(d.p) % (4 * sb))) % (4 * sb)) / sb);
+  // update: p, m, v move as 16-byte packets (a group: 4 fp32 or 8 bf16 elements).  A head of h
+  // elements must bring every buffer to the boundary its packets need: 16 bytes for p, m, v, one
+  // group's worth (at most 16 bytes) for the gradient and the parameter copy.
+  const int sdt = (sb == 4) ? ma::kF32 : ma::kBF16;
+  const size_t group = size_t(ma::step_group_elems(sdt));
+  const uint32_t h = uint32_t(((16 - (reinterpret_cast<uintptr_t>(d.p) % 16)) % 16) / sb);
   auto ok = [&](const void* ptr, size_t eb) {
-    return ((reinterpret_cast<uintptr_t>(ptr) + uint64_t(h) * eb) % (4 * eb)) == 0;
+    const size_t need = group * eb < 16 ? group * eb : 16;
+    return ((reinterpret_cast<uintptr_t>(ptr) + uint64_t(h) * eb) % need) == 0;
   };
   const bool vec = ok(d.m, sb) && ok(d.v, sb) && ok(d.g, gb) && (!has_lp || ok(d.lp, 2));
   d.step_head = vec ? h : 0;
   d.step_vec = vec ? 1 : 0;
   d.pad = 0;
+  const uint64_t chunk = ma::step_chunk_elems(sdt);
   if (vec) {
-    *step_chunks = (d.n <= h) ? 1 : ceil_div(d.n - h, ma::kStepChunkElems);
+    *step_chunks = (d.n <= h) ? 1 : ceil_div(d.n - h, chunk);
   } else {
-    *step_chunks = ceil_div(d.n, ma::kStepChunkElems);
+    *step_chunks = ceil_div(d.n, chunk);
   }
   return MA_OK;
 }

@@ -35,6 +35,9 @@ constexpr int kNoLp = 3;  // update kernel variant that writes no low-precision 
 #ifndef MA_NORM_MAP
 #define MA_NORM_MAP 0  // work-item assignment of the scan kernel (see WorkIter)
 #endif
+#ifndef MA_STEP_UNROLL_BF16
+#define MA_STEP_UNROLL_BF16 4  // 8-element groups per lane and tile when p, m, v are held in bf16
+#endif
 #ifndef MA_STEP_MAP
 #define MA_STEP_MAP 2  // work-item assignment of the update kernel (see WorkIter)
 #endif
@@ -42,7 +45,18 @@ constexpr int kNoLp = 3;  // update kernel variant that writes no low-precision 
 constexpr int kNormUnroll = MA_NORM_UNROLL;
 constexpr int kStepUnroll = MA_STEP_UNROLL;
 constexpr uint64_t kNormChunkBytes = uint64_t(kBlock) * 16 * kNormUnroll;  // per work item
-constexpr uint64_t kStepChunkElems = uint64_t(kBlock) * 4 * kStepUnroll;   // per work item
+
+// The update kernel moves p, m, v as 16-byte packets: a group is 4 consecutive elements for
+// fp32 states and 8 for bf16 states.  sdt: kF32 or kBF16.
+__host__ __device__ constexpr int step_group_elems(int sdt) { return sdt == kF32 ? 4 : 8; }
+__host__ __device__ constexpr int step_unroll(int sdt) {
+  return sdt == kF32 ? MA_STEP_UNROLL : MA_STEP_UNROLL_BF16;
+}
+// elements per work item of the update kernel
+__host__ __device__ constexpr uint64_t step_chunk_elems(int sdt) {
+  return uint64_t(kBlock) * step_group_elems(sdt) * step_unroll(sdt);
+}
+constexpr uint64_t kStepChunkElems = step_chunk_elems(kF32);
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -60,8 +74,8 @@ struct Desc {
   uint64_t norm_chunk0;  // index of this row's first scan work item
   uint64_t step_chunk0;  // index of this row's first update work item
   uint32_t norm_head;    // elements before the gradient's first 16-byte boundary
-  uint32_t step_head;    // elements before the common 4-element-group boundary
-  uint32_t step_vec;     // 1: the 4-wide path is usable after step_head elements
+  uint32_t step_head;    // elements before the group boundary common to all buffers
+  uint32_t step_vec;     // 1: the packet path is usable after step_head elements
   uint32_t pad;
 };
 static_assert(sizeof(Desc) == 80, "table row layout");

@@ -44,7 +44,7 @@ def _micro_grad(n, seed, gdt, scale, device="cuda"):
 
 # ---- gradient accumulation --------------------------------------------------------------------------
 
-ACC_SIZES = [0, 1, 3, 4, 5, 1023, 1024, 4095, 4096, 4097, 8193, 100_003, (1 << 20) + 7]
+ACC_SIZES = [0, 1, 3, 4, 5, 1023, 1024, 4095, 4096, 4097, 8191, 8192, 8193, 16385, 100_003, (1 << 20) + 7]
 
 
 @pytest.mark.parametrize("gdt", ["bf16", "f16", "f32"])
@@ -119,7 +119,7 @@ def _bf16_state(cfg, n):
     return st, p, m, v
 
 
-BF_SIZES = [0, 1, 3, 4, 5, 7, 8, 9, 1023, 1024, 4096, 4097, 8191, 100_003, (1 << 20) + 5]
+BF_SIZES = [0, 1, 3, 4, 5, 7, 8, 9, 15, 16, 17, 1023, 1024, 4096, 4097, 8191, 8192, 8193, 16385, 100_003, (1 << 20) + 5]
 
 
 @pytest.mark.parametrize("gdt,scale,clip", [("bf16", 1.0, 1.0), ("bf16", 1.0, 0.3), ("f16", 1024.0, 0.5)])
@@ -170,7 +170,8 @@ def test_bf16_state_misaligned():
     n = 30_001
     cfg = synth.FlatConfig("t", n + 16, seed=29, m_std=1e-3, v_std=1e-6, step=2, lr=1e-2)
     st, P, M, V = _bf16_state(cfg, n + 16)
-    for offs in [(1, 1, 1, 1), (3, 3, 3, 3), (1, 2, 3, 0), (0, 0, 0, 2), (4, 4, 4, 4)]:
+    for offs in [(1, 1, 1, 1), (3, 3, 3, 3), (1, 2, 3, 0), (0, 0, 0, 2), (4, 4, 4, 4), (7, 7, 7, 7), (8, 8, 8, 8),
+                 (5, 5, 5, 1), (0, 0, 0, 4), (8, 0, 0, 0)]:
         p, m, v, g = (t[o:o + n] for t, o in zip((P, M, V, st.g), offs))
         rp, rm, rv = synth.bits16(p), synth.bits16(m), synth.bits16(v)
         edges = [synth.bits16(t) for t in (P, M, V)]
