@@ -340,3 +340,69 @@ def test_multi_auto_iteration():
     assert ma.read_result(res)[0] is True
     assert ma.read_scaler(scaler) == (128.0, 0, 11, 1)
     assert host_f32(fl.p).tobytes() == before
+
+
+# ---- the whole iteration as one captured graph ----------------------------------------------------------
+
+def test_auto_iteration_replays_as_a_graph():
+    """Scan, gated update and loss-scale update read everything that changes from iteration to
+    iteration (scale, update number, gate) from device memory, so ONE captured graph serves every
+    iteration.  Replays are interleaved with eager work and synchronisations, include a skipped
+    iteration, and are checked against the oracle after every replay."""
+    n = 150_001
+    S0 = 1024.0
+    cfg = synth.FlatConfig("t", n, seed=91, gdt="f16", m_std=1e-4, v_std=1e-8, max_norm=0.05)
+    st = synth.make_flat(cfg, device="cuda")
+    ref = _host_state(st)
+    h_ref, h = oracle_hyper(cfg), _hyper(cfg)
+    state_ref, cfg_ref = oracle.scaler_state(scale=S0, step=7), oracle.scaler_cfg(window=2)
+    scaler, scfg = ma.new_scaler(S0, 7), ma.scaler_config(window=2)
+    ws, res = ma.workspace(), ma.new_result()
+    g_in = torch.zeros(n, dtype=torch.float16, device="cuda")     # the graph reads its gradient here
+
+    def iteration():
+        ma.overflow_norm_auto(g_in, scaler, res, ws)
+        ma.adamw_step_auto(st.p, st.m, st.v, g_in, st.p_lp, h, scaler, res, cfg.max_norm)
+        ma.scaler_update(scaler, res, scfg)
+
+    # one eager iteration first (also initialises everything the library caches per process)
+    def feed(it, bad):
+        g = _micro_grad(n, 700 + it, "f16", state_ref.scale)
+        if bad:
+            g.view(torch.int16)[it * 31 % n] = 0x7C00
+        g_in.copy_(g)
+        return host_grad(g)
+
+    def check(it, g_host, expect_overflow):
+        ov_ref, ss_ref = oracle.optimizer_step_auto(ref["p"], ref["m"], ref["v"], g_host, "f16", ref["lp"],
+                                                    "bf16", h_ref, state_ref, cfg_ref, cfg.max_norm)
+        torch.cuda.synchronize()
+        ov, ss = ma.read_result(res)
+        assert ov == ov_ref == expect_overflow, it
+        if not ov:
+            assert abs(ss - ss_ref) <= 1e-12 * ss_ref
+        assert ma.read_scaler(scaler) == (state_ref.scale, state_ref.good_steps, state_ref.step,
+                                          state_ref.skipped), it
+        assert_state_close(_host_state(st), ref, "graph iteration %d" % it)
+
+    gh = feed(0, False)
+    iteration()
+    check(0, gh, False)
+
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    gh = feed(1, False)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        iteration()
+    torch.cuda.synchronize()
+    # capturing does not execute: the state is still that of iteration 0
+    assert ma.read_scaler(scaler)[2] == 8
+    for it in range(1, 9):
+        bad = it in (3, 6)
+        gh = feed(it, bad)
+        graph.replay()
+        check(it, gh, bad)
+        # eager work of the program between replays
+        _ = (st.p[:1000] * 2).sum().item()
+    assert state_ref.skipped == 2
