@@ -81,6 +81,15 @@ typedef struct ma_tensor {
   size_t n;
 } ma_tensor;
 
+/* One tensor of a multi-tensor step with p, m, v held in bf16 (see ma_adamw_step_bf16). */
+typedef struct ma_tensor_bf16 {
+  void* p;          /* bf16 parameter, updated in place (it is its own low-precision copy) */
+  void* m;          /* bf16 first moment, updated in place */
+  void* v;          /* bf16 second moment, updated in place */
+  const void* grad; /* gradient in the list's gradient dtype, read only */
+  size_t n;
+} ma_tensor_bf16;
+
 /* Host-side handle of a prepared tensor list (plain data, caller-owned, copyable). */
 typedef struct ma_multi_plan {
   const void* table_dev; /* device table written by ma_multi_prepare */
@@ -91,7 +100,7 @@ typedef struct ma_multi_plan {
   int32_t gdt;
   int32_t pdt;
   uint32_t magic;
-  uint32_t reserved;
+  uint32_t sdt;          /* dtype of p, m, v: MA_F32, or MA_BF16 for a list from ma_multi_prepare_bf16 */
 } ma_multi_plan;
 
 /* Dynamic loss-scale state, 24 bytes, lives in device memory (Sec. III-C: when a value overflows,
@@ -260,6 +269,12 @@ size_t ma_multi_table_bytes(size_t count);
  * long as the tensors do not move.  Tensors with n == 0 are allowed and skipped.  count >= 1. */
 int ma_multi_prepare(const ma_tensor* list_host, size_t count, ma_dtype gdt, ma_dtype pdt,
                      void* table_dev, size_t table_bytes, void* stream, ma_multi_plan* plan_out);
+
+/* The same for a list whose p, m, v are held in bf16 and stored by truncation (Extended Experiments,
+ * bf16 half-precision optimizer).  The plan is accepted by every ma_multi_* call below; the update
+ * calls then run the step of ma_adamw_step_bf16 on every tensor. */
+int ma_multi_prepare_bf16(const ma_tensor_bf16* list_host, size_t count, ma_dtype gdt, void* table_dev,
+                          size_t table_bytes, void* stream, ma_multi_plan* plan_out);
 
 /* ma_overflow_norm over every tensor of the plan: one flag, one sum. */
 int ma_multi_overflow_norm(const ma_multi_plan* plan, float loss_scale, ma_norm_result* out_dev,

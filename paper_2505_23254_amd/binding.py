@@ -37,6 +37,11 @@ class Tensor(ctypes.Structure):
                 ("grad", ctypes.c_void_p), ("p_lp", ctypes.c_void_p), ("n", ctypes.c_size_t)]
 
 
+class TensorBF16(ctypes.Structure):
+    _fields_ = [("p", ctypes.c_void_p), ("m", ctypes.c_void_p), ("v", ctypes.c_void_p),
+                ("grad", ctypes.c_void_p), ("n", ctypes.c_size_t)]
+
+
 class ScalerConfig(ctypes.Structure):
     _fields_ = [("backoff", ctypes.c_float), ("growth", ctypes.c_float),
                 ("min_scale", ctypes.c_float), ("max_scale", ctypes.c_float),
@@ -47,7 +52,7 @@ class MultiPlanStruct(ctypes.Structure):
     _fields_ = [("table_dev", ctypes.c_void_p), ("entries", ctypes.c_uint64),
                 ("total_elems", ctypes.c_uint64), ("norm_chunks", ctypes.c_uint64),
                 ("step_chunks", ctypes.c_uint64), ("gdt", ctypes.c_int32), ("pdt", ctypes.c_int32),
-                ("magic", ctypes.c_uint32), ("reserved", ctypes.c_uint32)]
+                ("magic", ctypes.c_uint32), ("sdt", ctypes.c_uint32)]
 
 
 def _load() -> ctypes.CDLL:
@@ -72,6 +77,7 @@ def _load() -> ctypes.CDLL:
                                 ctypes.c_int),
         "ma_multi_table_bytes": ([sz], sz),
         "ma_multi_prepare": ([vp, sz, i32, i32, vp, sz, vp, vp], ctypes.c_int),
+        "ma_multi_prepare_bf16": ([vp, sz, i32, vp, sz, vp, vp], ctypes.c_int),
         "ma_multi_overflow_norm": ([vp, f32, vp, vp, sz, vp], ctypes.c_int),
         "ma_multi_adamw_step": ([vp, vp, i64, f32, f32, vp], ctypes.c_int),
         "ma_multi_adamw_step_gated": ([vp, vp, i64, f32, vp, f32, vp], ctypes.c_int),
@@ -239,6 +245,29 @@ class MultiPlan:
     @property
     def total(self) -> int:
         return int(self.plan.total_elems)
+
+
+class MultiPlanBF16(MultiPlan):
+    """A prepared tensor list whose p, m, v are bfloat16 tensors (ma_multi_prepare_bf16)."""
+
+    def __init__(self, p: Sequence[torch.Tensor], m: Sequence[torch.Tensor],
+                 v: Sequence[torch.Tensor], grad: Sequence[torch.Tensor], stream=None):
+        count = len(p)
+        if not (len(m) == count and len(v) == count and len(grad) == count) or count == 0:
+            raise ValueError("lists must be non-empty and of equal length")
+        gdt = _DT[grad[0].dtype]
+        arr = (TensorBF16 * count)()
+        for i in range(count):
+            if _DT[grad[i].dtype] != gdt:
+                raise TypeError("all tensors of a list share one gradient dtype")
+            pp, pm, pv, pg, _, n = _bf16_state_args(p[i], m[i], v[i], grad[i])
+            arr[i] = TensorBF16(pp, pm, pv, pg, n)
+        self._keep = (list(p), list(m), list(v), list(grad), None)
+        self.table = torch.empty(lib.ma_multi_table_bytes(count), dtype=torch.uint8,
+                                 device=p[0].device)
+        self.plan = MultiPlanStruct()
+        _check(lib.ma_multi_prepare_bf16(arr, count, gdt, self.table.data_ptr(), self.table.numel(),
+                                         _stream(stream), ctypes.byref(self.plan)))
 
 
 def multi_overflow_norm(plan: MultiPlan, loss_scale: float, out: torch.Tensor, ws: torch.Tensor,

@@ -151,6 +151,7 @@ int check_plan(const ma_multi_plan* plan) {
   if (!plan) return fail(MA_ERR_NULL, "plan is NULL");
   if (plan->magic != kPlanMagic) return fail(MA_ERR_ARG, "plan was not written by ma_multi_prepare");
   if (plan->entries > 0 && !plan->table_dev) return fail(MA_ERR_NULL, "plan has no device table");
+  if (!(plan->sdt == MA_F32 || plan->sdt == MA_BF16)) return fail(MA_ERR_ARG, "plan has an unknown state dtype");
   return MA_OK;
 }
 
@@ -230,7 +231,7 @@ int multi_step(const ma_multi_plan* plan, const StepRequest& q, void* stream) {
   if (int rc = check_plan(plan)) return rc;
   if (int rc = check_request(q)) return rc;
   if (plan->entries == 0) return MA_OK;
-  return step_common(nullptr, plan, plan->step_chunks, MA_F32, plan->gdt, plan->pdt, q, stream);
+  return step_common(nullptr, plan, plan->step_chunks, int(plan->sdt), plan->gdt, plan->pdt, q, stream);
 }
 
 int norm_common(const ma::Desc* row, const ma_multi_plan* plan, uint64_t chunks, int gdt,
@@ -270,6 +271,67 @@ int flat_norm(const void* grad, ma_dtype gdt, size_t n, float loss_scale, const 
     if (int rc = plan_row(d, gdt, false, &chunks, nullptr)) return rc;
   }
   return norm_common(&d, nullptr, chunks, gdt, loss_scale, scaler, out_dev, ws, ws_bytes, stream);
+}
+
+// Shared by the two prepare calls: `row(i, d)` fills the pointers and n of tensor i and returns
+// whether it carries a low-precision copy.
+template <class Row>
+int prepare_common(size_t count, ma_dtype gdt, int pdt, int sdt, void* table_dev, size_t table_bytes,
+                   void* stream, ma_multi_plan* plan_out, Row row) {
+  if (!plan_out) return fail(MA_ERR_NULL, "plan_out is NULL");
+  if (count < 1 || count > (1u << 24)) return fail(MA_ERR_ARG, "count must be in [1, 2^24]");
+  if (!dtype_ok(gdt)) return fail(MA_ERR_DTYPE, "unsupported gradient dtype %d", int(gdt));
+  if (!table_dev) return fail(MA_ERR_NULL, "table_dev is NULL");
+  if (!aligned(table_dev, 16)) return fail(MA_ERR_ALIGN, "table_dev must be 16-byte aligned");
+  if (table_bytes < ma_multi_table_bytes(count))
+    return fail(MA_ERR_ARG, "table too small: %zu < %zu bytes", table_bytes, ma_multi_table_bytes(count));
+
+  std::vector<ma::Desc> rows;
+  rows.reserve(count);
+  uint64_t norm_total = 0, step_total = 0, elems = 0;
+  int has_lp = -1;
+  for (size_t i = 0; i < count; ++i) {
+    ma::Desc d{};
+    const int lp = row(i, d) ? 1 : 0;
+    if (d.n == 0) continue;
+    if (!d.p || !d.m || !d.v || !d.g)
+      return fail(MA_ERR_NULL, "tensor %zu: p, m, v and grad must not be NULL", i);
+    if (has_lp < 0) has_lp = lp;
+    if (lp != has_lp)
+      return fail(MA_ERR_ARG, "tensor %zu: p_lp must be set for all tensors of a list or for none", i);
+    uint64_t nc = 0, sc = 0;
+    if (int rc = plan_row(d, gdt, lp != 0, &nc, &sc, sdt == MA_F32 ? 4 : 2)) {
+      char msg[400];
+      std::snprintf(msg, sizeof(msg), "%s", g_error);
+      return fail(rc, "tensor %zu: %s", i, msg);
+    }
+    d.norm_chunk0 = norm_total;
+    d.step_chunk0 = step_total;
+    norm_total += nc;
+    step_total += sc;
+    elems += d.n;
+    rows.push_back(d);
+  }
+  if (!rows.empty()) {
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e = hipMemcpyAsync(table_dev, rows.data(), rows.size() * sizeof(ma::Desc),
+                                  hipMemcpyHostToDevice, s);
+    if (e != hipSuccess) return fail_hip(e, "table upload");
+    e = hipStreamSynchronize(s);
+    if (e != hipSuccess) return fail_hip(e, "table upload (sync)");
+  }
+  ma_multi_plan plan{};
+  plan.table_dev = table_dev;
+  plan.entries = rows.size();
+  plan.total_elems = elems;
+  plan.norm_chunks = norm_total;
+  plan.step_chunks = step_total;
+  plan.gdt = gdt;
+  plan.pdt = (has_lp <= 0) ? ma::kNoLp : pdt;
+  plan.magic = kPlanMagic;
+  plan.sdt = uint32_t(sdt);
+  *plan_out = plan;
+  return MA_OK;
 }
 
 }  // namespace
@@ -468,68 +530,36 @@ size_t ma_multi_table_bytes(size_t count) { return (count ? count : 1) * sizeof(
 
 int ma_multi_prepare(const ma_tensor* list_host, size_t count, ma_dtype gdt, ma_dtype pdt,
                      void* table_dev, size_t table_bytes, void* stream, ma_multi_plan* plan_out) {
-  if (!list_host || !plan_out) return fail(MA_ERR_NULL, "list_host and plan_out must not be NULL");
-  if (count < 1 || count > (1u << 24)) return fail(MA_ERR_ARG, "count must be in [1, 2^24]");
-  if (!dtype_ok(gdt)) return fail(MA_ERR_DTYPE, "unsupported gradient dtype %d", int(gdt));
+  if (!list_host) return fail(MA_ERR_NULL, "list_host is NULL");
   if (!(pdt == MA_BF16 || pdt == MA_F16))
     return fail(MA_ERR_DTYPE, "low-precision parameter dtype must be MA_BF16 or MA_F16");
-  if (!table_dev) return fail(MA_ERR_NULL, "table_dev is NULL");
-  if (!aligned(table_dev, 16)) return fail(MA_ERR_ALIGN, "table_dev must be 16-byte aligned");
-  if (table_bytes < ma_multi_table_bytes(count))
-    return fail(MA_ERR_ARG, "table too small: %zu < %zu bytes", table_bytes, ma_multi_table_bytes(count));
+  return prepare_common(count, gdt, int(pdt), MA_F32, table_dev, table_bytes, stream, plan_out,
+                        [&](size_t i, ma::Desc& d) {
+                          const ma_tensor& t = list_host[i];
+                          d.p = t.p32;
+                          d.m = t.m;
+                          d.v = t.v;
+                          d.g = t.grad;
+                          d.lp = t.p_lp;
+                          d.n = t.n;
+                          return t.p_lp != nullptr;
+                        });
+}
 
-  std::vector<ma::Desc> rows;
-  rows.reserve(count);
-  uint64_t norm_total = 0, step_total = 0, elems = 0;
-  int has_lp = -1;
-  for (size_t i = 0; i < count; ++i) {
-    const ma_tensor& t = list_host[i];
-    if (t.n == 0) continue;
-    if (!t.p32 || !t.m || !t.v || !t.grad)
-      return fail(MA_ERR_NULL, "tensor %zu: p32, m, v and grad must not be NULL", i);
-    const int lp = t.p_lp != nullptr;
-    if (has_lp < 0) has_lp = lp;
-    if (lp != has_lp)
-      return fail(MA_ERR_ARG, "tensor %zu: p_lp must be set for all tensors of a list or for none", i);
-    ma::Desc d{};
-    d.p = t.p32;
-    d.m = t.m;
-    d.v = t.v;
-    d.g = t.grad;
-    d.lp = t.p_lp;
-    d.n = t.n;
-    uint64_t nc = 0, sc = 0;
-    if (int rc = plan_row(d, gdt, lp != 0, &nc, &sc)) {
-      char msg[400];
-      std::snprintf(msg, sizeof(msg), "%s", g_error);
-      return fail(rc, "tensor %zu: %s", i, msg);
-    }
-    d.norm_chunk0 = norm_total;
-    d.step_chunk0 = step_total;
-    norm_total += nc;
-    step_total += sc;
-    elems += t.n;
-    rows.push_back(d);
-  }
-  if (!rows.empty()) {
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = hipMemcpyAsync(table_dev, rows.data(), rows.size() * sizeof(ma::Desc),
-                                  hipMemcpyHostToDevice, s);
-    if (e != hipSuccess) return fail_hip(e, "table upload");
-    e = hipStreamSynchronize(s);
-    if (e != hipSuccess) return fail_hip(e, "table upload (sync)");
-  }
-  ma_multi_plan plan{};
-  plan.table_dev = table_dev;
-  plan.entries = rows.size();
-  plan.total_elems = elems;
-  plan.norm_chunks = norm_total;
-  plan.step_chunks = step_total;
-  plan.gdt = gdt;
-  plan.pdt = (has_lp == 0) ? ma::kNoLp : int(pdt);
-  plan.magic = kPlanMagic;
-  *plan_out = plan;
-  return MA_OK;
+int ma_multi_prepare_bf16(const ma_tensor_bf16* list_host, size_t count, ma_dtype gdt, void* table_dev,
+                          size_t table_bytes, void* stream, ma_multi_plan* plan_out) {
+  if (!list_host) return fail(MA_ERR_NULL, "list_host is NULL");
+  return prepare_common(count, gdt, ma::kNoLp, MA_BF16, table_dev, table_bytes, stream, plan_out,
+                        [&](size_t i, ma::Desc& d) {
+                          const ma_tensor_bf16& t = list_host[i];
+                          d.p = static_cast<float*>(t.p);
+                          d.m = static_cast<float*>(t.m);
+                          d.v = static_cast<float*>(t.v);
+                          d.g = t.grad;
+                          d.lp = nullptr;
+                          d.n = t.n;
+                          return false;
+                        });
 }
 
 int ma_multi_overflow_norm(const ma_multi_plan* plan, float loss_scale, ma_norm_result* out_dev,

@@ -108,6 +108,24 @@ def test_multi_argument_errors():
     assert ma.lib.ma_multi_adamw_step_gated(None, ctypes.byref(H), 1, 1.0, A, 1.0, None) == ma.MA_ERR_NULL
 
 
+def test_multi_bf16_argument_errors():
+    arr = (ma.TensorBF16 * 2)(ma.TensorBF16(A, A, A, A, 8), ma.TensorBF16(A, A + 1, A, A, 8))
+    plan = ma.MultiPlanStruct()
+    prep = ma.lib.ma_multi_prepare_bf16
+    assert ctypes.sizeof(ma.TensorBF16) == 40
+    assert prep(arr, 2, ma.MA_BF16, A, 160, None, ctypes.byref(plan)) == ma.MA_ERR_ALIGN
+    assert b"tensor 1" in ma.lib.ma_last_error()
+    assert prep(arr, 1, 9, A, 160, None, ctypes.byref(plan)) == ma.MA_ERR_DTYPE
+    assert prep(None, 1, ma.MA_BF16, A, 160, None, ctypes.byref(plan)) == ma.MA_ERR_NULL
+    assert prep(arr, 1, ma.MA_BF16, A, 8, None, ctypes.byref(plan)) == ma.MA_ERR_ARG
+    assert prep(arr, 1, ma.MA_BF16, A, 160, None, None) == ma.MA_ERR_NULL
+    nul = (ma.TensorBF16 * 1)(ma.TensorBF16(A, None, A, A, 8))
+    assert prep(nul, 1, ma.MA_BF16, A, 160, None, ctypes.byref(plan)) == ma.MA_ERR_NULL
+    # a plan with an unknown state dtype is refused
+    good = ma.MultiPlanStruct(A, 1, 8, 1, 1, ma.MA_BF16, ma.MA_BF16, 0x4D415450, 7)
+    assert ma.lib.ma_multi_adamw_step(ctypes.byref(good), ctypes.byref(H), 1, 1.0, 1.0, None) == ma.MA_ERR_ARG
+
+
 def test_host_step_scalars_match_oracle_bit_for_bit():
     import itertools
     for lr, b1, b2, eps, wd, bc in itertools.product((1e-5, 3e-2, 0.0), (0.9, 0.0, 0.8), (0.999, 0.95),

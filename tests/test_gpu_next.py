@@ -406,3 +406,49 @@ def test_auto_iteration_replays_as_a_graph():
         # eager work of the program between replays
         _ = (st.p[:1000] * 2).sum().item()
     assert state_ref.skipped == 2
+
+
+def test_multi_list_with_bf16_states():
+    """A ragged miniature of the 8B-shaped list with p, m, v held in bf16: one scan launch, one gated
+    update launch over the prepared list, against the oracle tensor by tensor; then an overflow."""
+    shapes = synth.scaled_shapes(synth.llama3_8b_shapes(), 4096, ragged=True)
+    cfg = synth.FlatConfig("t", 0, seed=53, m_std=1e-3, v_std=1e-6, step=6, lr=1e-2, weight_decay=0.1,
+                           eps=1e-6, max_norm=0.05)
+    for align in (64, 1):
+        ls = synth.make_list(shapes, cfg, device="cuda", align_elems=align)
+        shift = lambda t: (t.view(torch.int32) >> 16).to(torch.int16).view(torch.bfloat16).contiguous()
+        fp, fm, fv = shift(ls.flat.p), shift(ls.flat.m), shift(ls.flat.v)
+        offs = [t.data_ptr() // 4 - ls.flat.p.data_ptr() // 4 for t in ls.p]
+        cut = lambda buf: [buf[o:o + n] for o, (_, n) in zip(offs, shapes)]
+        P, M, V = cut(fp), cut(fm), cut(fv)
+        g_hosts = [host_grad(g) for g in ls.g]
+        ss_ref = 0.0
+        for g in g_hosts:
+            ov, ss = oracle.overflow_norm(g, "bf16")
+            assert not ov
+            ss_ref += ss
+        c_ref = oracle.clip_coef(ss_ref, float(np.float32(cfg.max_norm)))
+        assert c_ref < 1
+        refs = []
+        for i in range(len(shapes)):
+            rp, rm, rv = synth.bits16(P[i]), synth.bits16(M[i]), synth.bits16(V[i])
+            oracle.adamw_step_bf16(rp, rm, rv, g_hosts[i], "bf16", oracle_hyper(cfg), 6, 1.0, float(c_ref))
+            refs.append((rp, rm, rv))
+        plan = ma.MultiPlanBF16(P, M, V, ls.g)
+        assert plan.total == sum(n for _, n in shapes) and plan.plan.sdt == ma.MA_BF16
+        ws, res = ma.workspace(), ma.new_result()
+        ma.multi_overflow_norm(plan, 1.0, res, ws)
+        ma.multi_adamw_step_gated(plan, _hyper(cfg), 6, 1.0, res, cfg.max_norm)
+        ov, ss = ma.read_result(res)
+        assert not ov and abs(ss - ss_ref) <= 1e-12 * ss_ref
+        for i in range(len(shapes)):
+            for t, r in zip((P[i], M[i], V[i]), refs[i]):
+                assert np.array_equal(synth.bits16(t), r), (align, i, shapes[i])
+        # the ungated call with the host's coefficient does the same on a second copy
+        before = [synth.bits16(t) for t in (fp, fm, fv)]
+        ls.g[5].view(torch.int16)[0] = 0x7F80
+        ma.multi_overflow_norm(plan, 1.0, res, ws)
+        ma.multi_adamw_step_gated(plan, _hyper(cfg), 7, 1.0, res, cfg.max_norm)
+        assert ma.read_result(res)[0] is True
+        for t, b in zip((fp, fm, fv), before):
+            assert np.array_equal(synth.bits16(t), b)
