@@ -83,8 +83,18 @@ class Workload:
             except RuntimeError as e:      # e.g. another process holds most of the device
                 log("bench.py: whole-device arena not available (%s); falling back to a plain allocation" % e)
                 self.placement = placement = "plain"
-        place = (lambda nbytes, traffic: self.device_arena.window(nbytes, traffic)) \
-            if self.device_arena else (lambda nbytes, traffic: None)
+        def place(nbytes, traffic):
+            if self.device_arena is None:
+                return None
+            try:
+                return self.device_arena.window(nbytes, traffic)
+            except ValueError as e:        # the arena is smaller than the state
+                log("bench.py: %s; falling back to a plain allocation" % e)
+                self.device_arena = None
+                self.placement = "plain"
+                torch.cuda.empty_cache()
+                return None
+
         self.ws = ma.workspace()
         self.res = ma.new_result()
         self.t = 100
@@ -104,7 +114,7 @@ class Workload:
             self.n = self.plan.total
             self.kind = "multi"
             self.desc = ("290-tensor Llama-3-8B-shaped list, %d elements, fp32 p/m/v, bf16 grads "
-                         "~N(0,1e-3), clip 1.0; layout '%s', placement '%s'" % (self.n, layout, placement))
+                         "~N(0,1e-3), clip 1.0; layout '%s', placement '%s'" % (self.n, layout, self.placement))
         elif name == "qwen14b_4sub":
             cfg = synth.FlatConfig(name, 0, seed=4, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
             self.cfg = cfg
