@@ -143,7 +143,8 @@ class Workload:
                 self.micro = 4
                 self.kernel_label = "gradient accumulation into the fp32 flat buffer (2nd and later micro-batches)"
                 self.desc = ("fp32 flat gradient buffer n=%d, %d bf16 micro-batch gradients per step "
-                             "(first overwrites, the others add)" % (n, self.micro))
+                             "(first overwrites, the others add, the last add is fused with the "
+                             "overflow / norm scan of the buffer)" % (n, self.micro))
             buf = place(sum(sizes), list(zip(sizes, weights)))
             if buf is None:
                 buf = torch.empty(sum(sizes), dtype=torch.uint8, device="cuda")
@@ -216,8 +217,10 @@ class Workload:
             ma.grad_accumulate(self.acc, self.bg, first=True)
             if record:
                 ev[1].record()
-            for _ in range(self.micro - 1):
+            for _ in range(self.micro - 2):
                 ma.grad_accumulate(self.acc, self.bg, first=False)
+            # the last micro-batch of an iteration is accumulated and scanned in one pass
+            ma.grad_accumulate_scan(self.acc, self.bg, False, c.loss_scale, self.res, self.ws)
         elif self.kind == "flat":
             f = self.flat
             ma.overflow_norm(f.g, c.loss_scale, self.res, self.ws)

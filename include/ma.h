@@ -231,6 +231,16 @@ int ma_adamw_step_bf16_gated(void* p_bf16, void* m_bf16, void* v_bf16, const voi
 int ma_grad_accumulate(float* acc32, const void* grad, ma_dtype gdt, size_t n, int first,
                        void* stream);
 
+/* The same accumulation fused with the scan of ma_overflow_norm over the NEW contents of acc32
+ * (Algorithm 1 on fp32 values, mask 0x7F800000, and the sum of (acc_i / loss_scale)^2): for the last
+ * micro-batch of an iteration, so that the check that precedes the optimizer step (Sec. IV-A) does
+ * not read the flat buffer again.  Equivalent to ma_grad_accumulate followed by
+ * ma_overflow_norm(acc32, MA_F32, ...).  scaler_dev: NULL, or a loss-scale state in device memory
+ * whose scale replaces loss_scale.  n == 0 writes {0, 0.0}.  ws as for ma_overflow_norm. */
+int ma_grad_accumulate_scan(float* acc32, const void* grad, ma_dtype gdt, size_t n, int first,
+                            float loss_scale, const ma_scaler_state* scaler_dev,
+                            ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream);
+
 /* ---- dynamic loss scale on the device ------------------------------------------------------------ */
 
 /* Writes {scale, 0, applied_steps, 0} to *scaler_dev. */

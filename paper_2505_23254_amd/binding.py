@@ -85,6 +85,7 @@ def _load() -> ctypes.CDLL:
         "ma_adamw_step_bf16_gated": ([vp, vp, vp, vp, i32, sz, vp, i64, f32, vp, f32, vp],
                                      ctypes.c_int),
         "ma_grad_accumulate": ([vp, vp, i32, sz, ctypes.c_int, vp], ctypes.c_int),
+        "ma_grad_accumulate_scan": ([vp, vp, i32, sz, ctypes.c_int, f32, vp, vp, vp, sz, vp], ctypes.c_int),
         "ma_scaler_init": ([vp, f32, i64, vp], ctypes.c_int),
         "ma_scaler_update": ([vp, vp, vp, vp], ctypes.c_int),
         "ma_overflow_norm_auto": ([vp, i32, sz, vp, vp, vp, sz, vp], ctypes.c_int),
@@ -326,6 +327,20 @@ def grad_accumulate(acc32: torch.Tensor, grad: torch.Tensor, first: bool, stream
         raise ValueError("acc32 and grad must have the same number of elements")
     _check(lib.ma_grad_accumulate(_dev(acc32, "acc32"), _dev(grad, "grad"), _DT[grad.dtype],
                                   grad.numel(), int(bool(first)), _stream(stream)))
+
+
+def grad_accumulate_scan(acc32: torch.Tensor, grad: torch.Tensor, first: bool, loss_scale: float,
+                         out: torch.Tensor, ws: torch.Tensor, index: int = 0,
+                         scaler: Optional[torch.Tensor] = None, stream=None) -> None:
+    """ma_grad_accumulate_scan: accumulate, and scan the new contents of acc32 in the same pass."""
+    if acc32.dtype != torch.float32:
+        raise TypeError("acc32 must be float32")
+    if acc32.numel() != grad.numel():
+        raise ValueError("acc32 and grad must have the same number of elements")
+    _check(lib.ma_grad_accumulate_scan(_dev(acc32, "acc32"), _dev(grad, "grad"), _DT[grad.dtype],
+                                       grad.numel(), int(bool(first)), loss_scale,
+                                       None if scaler is None else _scaler(scaler), _slot(out, index),
+                                       _dev(ws, "ws"), ws.numel() * ws.element_size(), _stream(stream)))
 
 
 # ---- dynamic loss scale on the device ------------------------------------------------------------

@@ -474,11 +474,25 @@ int ma_adamw_step_bf16_gated(void* p, void* m, void* v, const void* grad, ma_dty
   return flat_step(p, m, v, grad, gdt, nullptr, MA_BF16, MA_BF16, n, q, stream);
 }
 
-int ma_grad_accumulate(float* acc32, const void* grad, ma_dtype gdt, size_t n, int first,
-                       void* stream) {
+namespace {
+
+int accumulate_common(float* acc32, const void* grad, ma_dtype gdt, size_t n, int first, bool scan,
+                      float loss_scale, const ma_scaler_state* scaler_dev, ma_norm_result* out_dev,
+                      void* ws, size_t ws_bytes, void* stream) {
   if (!dtype_ok(gdt)) return fail(MA_ERR_DTYPE, "unsupported gradient dtype %d", int(gdt));
-  if (n == 0) return MA_OK;
-  if (!acc32 || !grad) return fail(MA_ERR_NULL, "acc32 and grad must not be NULL");
+  if (scan) {
+    if (scaler_dev) {
+      if (!aligned(scaler_dev, 8)) return fail(MA_ERR_ALIGN, "scaler_dev must be 8-byte aligned");
+    } else if (int rc = check_scale(loss_scale)) {
+      return rc;
+    }
+    if (!out_dev) return fail(MA_ERR_NULL, "out_dev is NULL");
+    if (!aligned(out_dev, 8)) return fail(MA_ERR_ALIGN, "out_dev must be 8-byte aligned");
+    if (int rc = check_ws(ws, ws_bytes)) return rc;
+  } else if (n == 0) {
+    return MA_OK;
+  }
+  if (n > 0 && (!acc32 || !grad)) return fail(MA_ERR_NULL, "acc32 and grad must not be NULL");
   const size_t gb = elem_bytes(gdt);
   if (!aligned(acc32, 4) || !aligned(grad, gb))
     return fail(MA_ERR_ALIGN, "acc32 / grad not aligned to their element size");
@@ -486,10 +500,27 @@ int ma_grad_accumulate(float* acc32, const void* grad, ma_dtype gdt, size_t n, i
   const uint32_t vec = ((reinterpret_cast<uintptr_t>(grad) + uint64_t(h) * gb) % (4 * gb)) == 0;
   int cus = 0;
   if (int rc = device_cus(&cus)) return rc;
-  hipError_t e = ma::launch_accumulate(acc32, grad, gdt, n, vec ? h : 0, vec, first != 0, cus,
-                                       static_cast<hipStream_t>(stream));
+  const double inv = (scan && !scaler_dev) ? 1.0 / (double(loss_scale) * double(loss_scale)) : 1.0;
+  hipError_t e = ma::launch_accumulate(
+      acc32, grad, gdt, n, vec ? h : 0, vec, first != 0, scan ? static_cast<ma::NormPartial*>(ws) : nullptr,
+      inv, reinterpret_cast<const ma::ScalerState*>(scaler_dev), reinterpret_cast<ma::NormResult*>(out_dev),
+      cus, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail_hip(e, "accumulate kernel launch");
   return MA_OK;
+}
+
+}  // namespace
+
+int ma_grad_accumulate(float* acc32, const void* grad, ma_dtype gdt, size_t n, int first,
+                       void* stream) {
+  return accumulate_common(acc32, grad, gdt, n, first, false, 1.0f, nullptr, nullptr, nullptr, 0, stream);
+}
+
+int ma_grad_accumulate_scan(float* acc32, const void* grad, ma_dtype gdt, size_t n, int first,
+                            float loss_scale, const ma_scaler_state* scaler_dev,
+                            ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream) {
+  return accumulate_common(acc32, grad, gdt, n, first, true, loss_scale, scaler_dev, out_dev, ws,
+                           ws_bytes, stream);
 }
 
 int ma_scaler_init(ma_scaler_state* scaler_dev, float scale, int64_t applied_steps, void* stream) {

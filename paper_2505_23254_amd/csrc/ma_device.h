@@ -267,4 +267,74 @@ __device__ __forceinline__ uint32_t wave_max_pattern(uint32_t x) {
   return x;
 }
 
+// ---- per-lane state of the gradient scan and its block-level fold -----------------------------------
+// Flag: the running maximum of the sign-stripped bit patterns (a pattern has an all-ones exponent
+// exactly when, with the sign removed, it is >= the pattern of infinity).  Sum: each element is
+// widened exactly, squared and accumulated in fp64.
+template <int GDT>
+struct NormAcc {
+  double a0 = 0.0, a1 = 0.0;
+  uint32_t mx = 0;
+
+  __device__ __forceinline__ void word(uint32_t w) {
+    if constexpr (GDT == kF32) {
+      mx = max_pattern<false>(mx, w & 0x7FFFFFFFu);
+      const double x = static_cast<double>(bits_to_f32(w));
+      a0 = __builtin_fma(x, x, a0);
+    } else {
+      mx = max_pattern<true>(mx, w & 0x7FFF7FFFu);
+      const double lo = static_cast<double>(widen16<GDT>(w & 0xFFFFu));
+      const double hi = static_cast<double>(widen16<GDT>(w >> 16));
+      a0 = __builtin_fma(lo, lo, a0);
+      a1 = __builtin_fma(hi, hi, a1);
+    }
+  }
+  __device__ __forceinline__ void vec(u32x4 w) {
+    word(w.x);
+    word(w.y);
+    word(w.z);
+    word(w.w);
+  }
+  // one element given by index into the raw gradient buffer
+  __device__ __forceinline__ void element(MA_GLOBAL const char* g, uint64_t i) {
+    if constexpr (GDT == kF32) {
+      word(reinterpret_cast<MA_GLOBAL const uint32_t*>(g)[i]);
+    } else {
+      const uint32_t h = reinterpret_cast<MA_GLOBAL const uint16_t*>(g)[i];
+      mx = max_pattern<true>(mx, h & 0x7FFFu);
+      const double x = static_cast<double>(widen16<GDT>(h));
+      a0 = __builtin_fma(x, x, a0);
+    }
+  }
+};
+
+// Block-level fold of the per-lane accumulators; thread 0 writes the block's partial.
+template <int GDT>
+__device__ __forceinline__ void norm_block_finish(NormAcc<GDT>& acc, NormPartial* partials) {
+  __shared__ double s_sum[kBlock / kWave];
+  __shared__ uint32_t s_max[kBlock / kWave];
+  const double ws = wave_sum(acc.a0 + acc.a1);
+  const uint32_t wm = wave_max_pattern<GDT != kF32>(acc.mx);
+  const int wave = threadIdx.x / kWave;
+  if ((threadIdx.x & (kWave - 1)) == 0) {
+    s_sum[wave] = ws;
+    s_max[wave] = wm;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = s_sum[0];
+    uint32_t mx = s_max[0];
+#pragma unroll
+    for (int k = 1; k < kBlock / kWave; ++k) {
+      t += s_sum[k];
+      mx = max_pattern<GDT != kF32>(mx, s_max[k]);
+    }
+    NormPartial out;
+    out.sum = t;
+    out.maxabs = mx;
+    out.pad = 0;
+    partials[blockIdx.x] = out;
+  }
+}
+
 }  // namespace ma

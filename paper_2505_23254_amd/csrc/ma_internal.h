@@ -27,6 +27,10 @@ hipError_t launch_norm(const Desc* row_host, const Desc* table_dev, uint32_t row
                        int gdt, double inv_scale_sq, const ScalerState* scaler, NormPartial* partials,
                        NormResult* out, int device_cus, hipStream_t stream);
 
+// Second level of the scan: one block adds `count` per-block partials in index order.
+hipError_t launch_norm_finalize(const NormPartial* partials, uint32_t count, int gdt, double inv_scale_sq,
+                                const ScalerState* scaler, NormResult* out, hipStream_t stream);
+
 hipError_t launch_norm_combine(const NormResult* parts, uint32_t count, NormResult* out,
                                hipStream_t stream);
 
@@ -40,7 +44,11 @@ hipError_t launch_scaler_update(ScalerState* state, const NormResult* gate, cons
                                 hipStream_t stream);
 
 // acc (fp32) = first ? widen(g) : acc + widen(g) over n elements; head / vec as planned by the host.
+// With partials != null the same pass also scans the NEW contents of acc (flag and sum of squares
+// of fp32 values) and `out` receives the result.
 hipError_t launch_accumulate(float* acc, const void* g, int gdt, uint64_t n, uint32_t head,
-                             uint32_t vec, int first, int device_cus, hipStream_t stream);
+                             uint32_t vec, int first, NormPartial* partials, double inv_scale_sq,
+                             const ScalerState* scaler, NormResult* out, int device_cus,
+                             hipStream_t stream);
 
 }  // namespace ma

@@ -196,6 +196,16 @@ def test_bf16_state_and_accumulate_argument_errors():
     assert acc(A, A + 2, ma.MA_F32, 8, 0, None) == ma.MA_ERR_ALIGN
     assert acc(A, A, 4, 8, 0, None) == ma.MA_ERR_DTYPE
     assert acc(A, A, ma.MA_BF16, 0, 0, None) == ma.MA_OK
+    fused = ma.lib.ma_grad_accumulate_scan
+    ws = ma.lib.ma_workspace_bytes()
+    assert fused(A, A, ma.MA_BF16, 8, 0, 1.0, None, None, A, ws, None) == ma.MA_ERR_NULL       # out_dev
+    assert fused(A, A, ma.MA_BF16, 8, 0, 1.0, None, A, None, ws, None) == ma.MA_ERR_NULL       # ws
+    assert fused(A, A, ma.MA_BF16, 8, 0, 1.0, None, A, A, ws - 16, None) == ma.MA_ERR_ARG
+    assert fused(A, A, ma.MA_BF16, 8, 0, 0.0, None, A, A, ws, None) == ma.MA_ERR_ARG           # scale
+    assert fused(A, A, ma.MA_BF16, 8, 0, 0.0, A + 4, A, A, ws, None) == ma.MA_ERR_ALIGN        # scaler
+    assert fused(None, A, ma.MA_BF16, 8, 0, 1.0, None, A, A, ws, None) == ma.MA_ERR_NULL
+    assert fused(A, A + 1, ma.MA_BF16, 8, 0, 1.0, None, A, A, ws, None) == ma.MA_ERR_ALIGN
+    assert fused(A, A, 6, 8, 0, 1.0, None, A, A, ws, None) == ma.MA_ERR_DTYPE
 
 
 def test_scaler_argument_errors():

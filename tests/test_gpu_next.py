@@ -452,3 +452,56 @@ def test_multi_list_with_bf16_states():
         assert ma.read_result(res)[0] is True
         for t, b in zip((fp, fm, fv), before):
             assert np.array_equal(synth.bits16(t), b)
+
+
+@pytest.mark.parametrize("gdt", ["bf16", "f16", "f32"])
+def test_accumulate_fused_with_scan(gdt):
+    """The last micro-batch accumulated and scanned in one pass: the buffer equals the oracle's, and
+    {overflow, sumsq} equals the oracle's scan of the accumulated fp32 buffer; also through views
+    that force the scalar path, with a device-resident scale, and with planted non-finite values."""
+    ws = ma.workspace()
+    S = 256.0
+    for n in [0, 1, 3, 5, 1023, 4096, 4097, 8193, 100_003, (1 << 20) + 7]:
+        for off_acc, off_g in ((0, 0), (1, 1), (1, 2)):
+            base = torch.zeros(n + 4, dtype=torch.float32, device="cuda")
+            acc = base[off_acc:off_acc + n]
+            ref = np.zeros(n, np.float32)
+            res = ma.new_result(2)
+            for k in range(3):
+                gfull = _micro_grad(n + 4, 2000 + 7 * k + n % 13, gdt, S)
+                g = gfull[off_g:off_g + n]
+                oracle.grad_accumulate(ref, host_grad(g), gdt, first=(k == 0))
+                if k < 2:
+                    ma.grad_accumulate(acc, g, first=(k == 0))
+                else:
+                    ma.grad_accumulate_scan(acc, g, False, S, res, ws)
+            assert np.array_equal(host_f32(acc).view(np.uint32), ref.view(np.uint32)), (n, off_acc, off_g)
+            ov_ref, ss_ref = oracle.overflow_norm(ref, "f32", S)
+            ov, ss = ma.read_result(res)
+            assert ov == ov_ref == False
+            assert abs(ss - ss_ref) <= 1e-12 * max(ss_ref, 1e-300), (n, ss, ss_ref)
+            # the stand-alone scan of the same buffer agrees (same kernels' arithmetic, other order)
+            ma.overflow_norm(acc, S, res, ws, index=1)
+            assert abs(ma.read_result(res, 1)[1] - ss) <= 1e-12 * max(ss, 1e-300)
+    # `first` with scan, scale taken from device memory, and an overflow entering with the micro-batch
+    n = 50_001
+    acc = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
+    g = _micro_grad(n, 77, gdt, S)
+    scaler = ma.new_scaler(S, 0)
+    res = ma.new_result(2)
+    ma.grad_accumulate_scan(acc, g, True, 1.0, res, ws, scaler=scaler)
+    ref = np.full(n, np.nan, np.float32)
+    oracle.grad_accumulate(ref, host_grad(g), gdt, first=True)
+    ov_ref, ss_ref = oracle.overflow_norm(ref, "f32", S)
+    ov, ss = ma.read_result(res)
+    assert not ov and not ov_ref and abs(ss - ss_ref) <= 1e-12 * ss_ref
+    if gdt != "f32":
+        bits = synth.NONFINITE_BITS[gdt][1]
+        g.view(torch.int16)[n - 2] = bits - 0x10000
+    else:
+        g[n - 2] = float("-inf")
+    ma.grad_accumulate_scan(acc, g, False, S, res, ws, index=1)
+    assert ma.read_result(res, 1)[0] is True
+    oracle.grad_accumulate(ref, host_grad(g), gdt, first=False)
+    assert oracle.overflow_norm(ref, "f32", S)[0] is True
+    assert np.array_equal(host_f32(acc).view(np.uint32), ref.view(np.uint32))
