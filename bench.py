@@ -41,8 +41,8 @@ SCAN_BYTES_PER_PARAM = 2.0     # scan kernel: read g
 # profiles/hbm_traffic_counters__llama3_8b.txt).  Valid only for the kernel sources they were taken
 # with: when the digest of the kernel sources differs, the figure is reported as null.
 MEASURED_TRAFFIC = {
-    "kernel_sha256": "d8209febd6892a383422b30bab7058e74f64fa9a39de46c496dc0165f67a4a7a",
-    "llama3_8b": 224855360654,
+    "kernel_sha256": "7246fe4b9a286dd881c0f8d14788226fbfd261d7175316fe305bbdd093c3a39f",
+    "llama3_8b": 224855540152,
 }
 
 
