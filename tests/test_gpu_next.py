@@ -122,12 +122,16 @@ def _bf16_state(cfg, n):
 BF_SIZES = [0, 1, 3, 4, 5, 7, 8, 9, 15, 16, 17, 1023, 1024, 4096, 4097, 8191, 8192, 8193, 16385, 100_003, (1 << 20) + 5]
 
 
-@pytest.mark.parametrize("gdt,scale,clip", [("bf16", 1.0, 1.0), ("bf16", 1.0, 0.3), ("f16", 1024.0, 0.5)])
+@pytest.mark.parametrize("gdt,scale,clip", [("bf16", 1.0, 1.0), ("bf16", 1.0, 0.3), ("f16", 1024.0, 0.5),
+                                            ("f32", 8.0, 0.7)])
 def test_bf16_state_step_sizes(gdt, scale, clip):
     for n in BF_SIZES:
-        cfg = synth.FlatConfig("t", n, seed=200 + n % 89, gdt=gdt, loss_scale=scale, m_std=1e-3,
-                               v_std=1e-6, step=7, lr=1e-2, weight_decay=0.1, eps=1e-6)
+        cfg = synth.FlatConfig("t", n, seed=200 + n % 89, gdt="bf16" if gdt == "f32" else gdt,
+                               loss_scale=scale, m_std=1e-3, v_std=1e-6, step=7, lr=1e-2, weight_decay=0.1,
+                               eps=1e-6)
         st, p, m, v = _bf16_state(cfg, n)
+        if gdt == "f32":                  # fp32 gradients: the accumulated flat buffer as input
+            st.g = st.g.to(torch.float32) * 1.0001
         g_host = host_grad(st.g)
         rp, rm, rv = synth.bits16(p), synth.bits16(m), synth.bits16(v)
         moved_from = rp.copy()
