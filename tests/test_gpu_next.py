@@ -509,3 +509,42 @@ def test_accumulate_fused_with_scan(gdt):
     oracle.grad_accumulate(ref, host_grad(g), gdt, first=False)
     assert oracle.overflow_norm(ref, "f32", S)[0] is True
     assert np.array_equal(host_f32(acc).view(np.uint32), ref.view(np.uint32))
+
+
+def test_multi_list_with_fp32_gradients():
+    """The tensor list fed from an accumulated fp32 gradient buffer (Algorithm 1's own dtype): one
+    scan launch with the 0x7F800000 mask, one gated update launch, fp16 parameter copies."""
+    shapes = synth.scaled_shapes(synth.llama3_8b_shapes(), 8192, ragged=True)
+    cfg = synth.FlatConfig("t", 0, seed=57, m_std=1e-4, v_std=1e-8, step=12, pdt="f16", max_norm=0.03)
+    S = 32.0
+    for align in (64, 1):
+        ls = synth.make_list(shapes, cfg, device="cuda", align_elems=align)
+        total = ls.flat.p.numel()
+        g32_flat = (ls.flat.g.to(torch.float32) * (S * 1.0003)).contiguous()
+        offs = [t.data_ptr() // 4 - ls.flat.p.data_ptr() // 4 for t in ls.p]
+        G32 = [g32_flat[o:o + n] for o, (_, n) in zip(offs, shapes)]
+        ss_ref, refs = 0.0, []
+        for g in G32:
+            ov, ss = oracle.overflow_norm(host_f32(g), "f32", S)
+            assert not ov
+            ss_ref += ss
+        c_ref = oracle.clip_coef(ss_ref, float(np.float32(cfg.max_norm)))
+        assert c_ref < 1
+        for i in range(len(shapes)):
+            r = dict(p=host_f32(ls.p[i]), m=host_f32(ls.m[i]), v=host_f32(ls.v[i]), pdt="f16")
+            r["lp"] = oracle.adamw_step(r["p"], r["m"], r["v"], host_f32(G32[i]), "f32", "f16",
+                                        oracle_hyper(cfg), 12, S, float(c_ref))
+            refs.append(r)
+        plan = ma.MultiPlan(ls.p, ls.m, ls.v, G32, ls.p_lp)
+        ws, res = ma.workspace(), ma.new_result()
+        ma.multi_overflow_norm(plan, S, res, ws)
+        ma.multi_adamw_step_gated(plan, _hyper(cfg), 12, S, res, cfg.max_norm)
+        ov, ss = ma.read_result(res)
+        assert not ov and abs(ss - ss_ref) <= 1e-12 * ss_ref
+        for i in range(len(shapes)):
+            got = dict(p=host_f32(ls.p[i]), m=host_f32(ls.m[i]), v=host_f32(ls.v[i]),
+                       lp=synth.bits16(ls.p_lp[i]))
+            assert_state_close(got, refs[i], "tensor %d" % i)
+        G32[11][0] = float("inf")
+        ma.multi_overflow_norm(plan, S, res, ws)
+        assert ma.read_result(res)[0] is True
