@@ -51,7 +51,8 @@ typedef enum ma_status {
   MA_ERR_DTYPE = -2, /* dtype not supported in this position */
   MA_ERR_ALIGN = -3, /* pointer not aligned to its element size */
   MA_ERR_ARG = -4,   /* value out of range (see each call) or workspace too small */
-  MA_ERR_HIP = -5    /* the HIP runtime reported an error; text in ma_last_error() */
+  MA_ERR_HIP = -5,   /* the HIP runtime reported an error; text in ma_last_error() */
+  MA_ERR_FULL = -6   /* ma_pool_acquire: every buffer of the sub-pool is in use */
 } ma_status;
 
 /* Result of the gradient scan, 16 bytes, lives in device memory. */
@@ -305,6 +306,62 @@ int ma_multi_overflow_norm_auto(const ma_multi_plan* plan, const ma_scaler_state
 int ma_multi_adamw_step_auto(const ma_multi_plan* plan, const ma_hyper* hyper,
                              const ma_scaler_state* scaler_dev, const ma_norm_result* gate_dev,
                              float max_norm, void* stream);
+
+/* ---- host side: parameter buffer pool and pinned sizes (plain host code, no GPU needed) ---------- */
+
+/* Shapes of the tensors that travel through the parameter buffer pool (Sec. IV-B): embedding and
+ * LM head are vocab x hidden, the three feed-forward projections intermediate x hidden, K and V
+ * kv_dim x hidden (kv_dim = KV heads x head size), Q and O q_dim x hidden. */
+typedef struct ma_model_dims {
+  uint64_t vocab, hidden, intermediate, kv_dim, q_dim;
+} ma_model_dims;
+
+enum { MA_POOL_EMBED = 0, MA_POOL_FFN = 1, MA_POOL_KV = 2, MA_POOL_QO = 3 };
+
+/* The adaptive pool of Sec. IV-B and, for comparison, the original uniform pool of Sec. III-A.
+ * Sub-pool k holds count[k] buffers of buffer_bytes[k] bytes starting at byte offset[k] of ONE
+ * monolithic allocation of total_bytes. */
+typedef struct ma_pool_layout {
+  uint64_t count[4];             /* 2, 3N, 2N, 2N for N transformer blocks in flight */
+  uint64_t buffer_bytes[4];      /* this process's shard of one tensor, rounded up to `align` */
+  uint64_t offset[4];
+  uint64_t total_bytes;          /* the adaptive pool */
+  uint64_t uniform_count;        /* 2 + 7N buffers ... */
+  uint64_t uniform_buffer_bytes; /* ... each as large as the largest of the four kinds */
+  uint64_t uniform_bytes;        /* the original pool */
+} ma_pool_layout;
+
+/* Sizes both pools.  blocks_in_flight = N >= 1; elem_bytes = bytes of a low-precision parameter
+ * (1, 2 or 4); partitions >= 1: number of data-parallel processes a tensor is sharded over (each
+ * process buffers its own ceil(numel / partitions) elements); align: power of two every buffer size
+ * is rounded up to (1 = exact sizes, 4096 = the granularity of a pinned allocation). */
+int ma_pool_layout_compute(const ma_model_dims* dims, uint32_t blocks_in_flight, uint32_t elem_bytes,
+                           uint32_t partitions, uint32_t align, ma_pool_layout* out_host);
+
+/* Logical management of the monolithic allocation (Sec. IV-B): a table from the caller's key (one
+ * per tensor being fetched) to the buffer it holds.  The pool hands out byte offsets; the memory
+ * itself belongs to the caller.  Not thread-safe: one pool per thread, or lock around it. */
+typedef struct ma_pool ma_pool;
+int ma_pool_create(const ma_pool_layout* layout, ma_pool** pool_out);
+void ma_pool_destroy(ma_pool* pool);
+/* Takes a free buffer of sub-pool `kind` (MA_POOL_*) for `key`.  MA_ERR_ARG if the key already
+ * holds a buffer, MA_ERR_FULL if the sub-pool has none left.  bytes_out may be NULL. */
+int ma_pool_acquire(ma_pool* pool, uint64_t key, int kind, uint64_t* offset_out, uint64_t* bytes_out);
+int ma_pool_lookup(const ma_pool* pool, uint64_t key, uint64_t* offset_out, uint64_t* bytes_out);
+int ma_pool_release(ma_pool* pool, uint64_t key);
+uint64_t ma_pool_in_use(const ma_pool* pool, int kind);
+
+/* Bytes a pinned allocation of `request` bytes occupies under a size policy (Sec. III-B, Sec. IV-C):
+ * MA_PINNED_PAGE rounds up to 4096 bytes, the granularity DMA needs; MA_PINNED_POW2 rounds up to the
+ * next power of two, as a caching host allocator does. */
+enum { MA_PINNED_PAGE = 0, MA_PINNED_POW2 = 1 };
+uint64_t ma_pinned_bytes(uint64_t request, int policy);
+
+/* Page-locked host memory of exactly ma_pinned_bytes(bytes, MA_PINNED_PAGE) bytes, usable for DMA
+ * from every device context (Sec. IV-C: static, long-lived offloading buffers get their exact size).
+ * The caller frees it with ma_pinned_free.  These two calls need the HIP runtime. */
+int ma_pinned_alloc(size_t bytes, void** host_ptr_out);
+int ma_pinned_free(void* host_ptr);
 
 #ifdef __cplusplus
 }

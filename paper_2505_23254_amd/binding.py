@@ -17,7 +17,9 @@ LIB_PATH = os.path.join(_HERE, "libma_step.so")
 MA_F32, MA_BF16, MA_F16 = 0, 1, 2
 _DT = {torch.float32: MA_F32, torch.bfloat16: MA_BF16, torch.float16: MA_F16}
 
-MA_OK, MA_ERR_NULL, MA_ERR_DTYPE, MA_ERR_ALIGN, MA_ERR_ARG, MA_ERR_HIP = 0, -1, -2, -3, -4, -5
+MA_OK, MA_ERR_NULL, MA_ERR_DTYPE, MA_ERR_ALIGN, MA_ERR_ARG, MA_ERR_HIP, MA_ERR_FULL = 0, -1, -2, -3, -4, -5, -6
+MA_POOL_EMBED, MA_POOL_FFN, MA_POOL_KV, MA_POOL_QO = 0, 1, 2, 3
+MA_PINNED_PAGE, MA_PINNED_POW2 = 0, 1
 
 
 class MaError(RuntimeError):
@@ -46,6 +48,17 @@ class ScalerConfig(ctypes.Structure):
     _fields_ = [("backoff", ctypes.c_float), ("growth", ctypes.c_float),
                 ("min_scale", ctypes.c_float), ("max_scale", ctypes.c_float),
                 ("window", ctypes.c_int32)]
+
+
+class ModelDims(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_uint64) for k in ("vocab", "hidden", "intermediate", "kv_dim", "q_dim")]
+
+
+class PoolLayout(ctypes.Structure):
+    _fields_ = [("count", ctypes.c_uint64 * 4), ("buffer_bytes", ctypes.c_uint64 * 4),
+                ("offset", ctypes.c_uint64 * 4), ("total_bytes", ctypes.c_uint64),
+                ("uniform_count", ctypes.c_uint64), ("uniform_buffer_bytes", ctypes.c_uint64),
+                ("uniform_bytes", ctypes.c_uint64)]
 
 
 class MultiPlanStruct(ctypes.Structure):
@@ -78,6 +91,17 @@ def _load() -> ctypes.CDLL:
         "ma_multi_table_bytes": ([sz], sz),
         "ma_multi_prepare": ([vp, sz, i32, i32, vp, sz, vp, vp], ctypes.c_int),
         "ma_multi_prepare_bf16": ([vp, sz, i32, vp, sz, vp, vp], ctypes.c_int),
+        "ma_pool_layout_compute": ([vp, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32, ctypes.c_uint32, vp],
+                                   ctypes.c_int),
+        "ma_pool_create": ([vp, vp], ctypes.c_int),
+        "ma_pool_destroy": ([vp], None),
+        "ma_pool_acquire": ([vp, ctypes.c_uint64, ctypes.c_int, vp, vp], ctypes.c_int),
+        "ma_pool_lookup": ([vp, ctypes.c_uint64, vp, vp], ctypes.c_int),
+        "ma_pool_release": ([vp, ctypes.c_uint64], ctypes.c_int),
+        "ma_pool_in_use": ([vp, ctypes.c_int], ctypes.c_uint64),
+        "ma_pinned_bytes": ([ctypes.c_uint64, ctypes.c_int], ctypes.c_uint64),
+        "ma_pinned_alloc": ([sz, vp], ctypes.c_int),
+        "ma_pinned_free": ([vp], ctypes.c_int),
         "ma_multi_overflow_norm": ([vp, f32, vp, vp, sz, vp], ctypes.c_int),
         "ma_multi_adamw_step": ([vp, vp, i64, f32, f32, vp], ctypes.c_int),
         "ma_multi_adamw_step_gated": ([vp, vp, i64, f32, vp, f32, vp], ctypes.c_int),
@@ -397,3 +421,63 @@ def multi_adamw_step_auto(plan: MultiPlan, h: Hyper, scaler: torch.Tensor, gate:
                           max_norm: float, index: int = 0, stream=None) -> None:
     _check(lib.ma_multi_adamw_step_auto(ctypes.byref(plan.plan), ctypes.byref(h), _scaler(scaler),
                                         _slot(gate, index), max_norm, _stream(stream)))
+
+
+# ---- host side: parameter buffer pool and pinned sizes ------------------------------------------------
+
+def pool_layout(vocab: int, hidden: int, intermediate: int, kv_dim: int, q_dim: int,
+                blocks_in_flight: int = 1, elem_bytes: int = 2, partitions: int = 1,
+                align: int = 1) -> PoolLayout:
+    """ma_pool_layout_compute: sizes of the adaptive and of the uniform parameter buffer pool."""
+    dims = ModelDims(vocab, hidden, intermediate, kv_dim, q_dim)
+    out = PoolLayout()
+    _check(lib.ma_pool_layout_compute(ctypes.byref(dims), blocks_in_flight, elem_bytes, partitions,
+                                      align, ctypes.byref(out)))
+    return out
+
+
+class BufferPool:
+    """ma_pool_*: hands out byte offsets into one monolithic allocation, keyed by the caller."""
+
+    def __init__(self, layout: PoolLayout):
+        self._h = ctypes.c_void_p()
+        _check(lib.ma_pool_create(ctypes.byref(layout), ctypes.byref(self._h)))
+
+    def acquire(self, key: int, kind: int):
+        off, nb = ctypes.c_uint64(), ctypes.c_uint64()
+        _check(lib.ma_pool_acquire(self._h, key, kind, ctypes.byref(off), ctypes.byref(nb)))
+        return off.value, nb.value
+
+    def lookup(self, key: int):
+        off, nb = ctypes.c_uint64(), ctypes.c_uint64()
+        _check(lib.ma_pool_lookup(self._h, key, ctypes.byref(off), ctypes.byref(nb)))
+        return off.value, nb.value
+
+    def release(self, key: int) -> None:
+        _check(lib.ma_pool_release(self._h, key))
+
+    def in_use(self, kind: int) -> int:
+        return lib.ma_pool_in_use(self._h, kind)
+
+    def close(self) -> None:
+        if self._h:
+            lib.ma_pool_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        self.close()
+
+
+def pinned_bytes(request: int, policy: int = MA_PINNED_PAGE) -> int:
+    return lib.ma_pinned_bytes(request, policy)
+
+
+def pinned_alloc(nbytes: int) -> int:
+    """ma_pinned_alloc: address of page-locked host memory of exactly the page-rounded size."""
+    p = ctypes.c_void_p()
+    _check(lib.ma_pinned_alloc(nbytes, ctypes.byref(p)))
+    return p.value
+
+
+def pinned_free(ptr: int) -> None:
+    _check(lib.ma_pinned_free(ptr))

@@ -342,6 +342,28 @@ int ma_version(void) { return 100; }
 
 const char* ma_last_error(void) { return g_error; }
 
+// error channel for the host-only translation unit; not exported
+__attribute__((visibility("hidden"))) int ma_set_error_message(int code, const char* msg) {
+  return fail(code, "%s", msg);
+}
+
+int ma_pinned_alloc(size_t bytes, void** host_ptr_out) {
+  if (!host_ptr_out) return fail(MA_ERR_NULL, "host_ptr_out is NULL");
+  if (bytes == 0) return fail(MA_ERR_ARG, "bytes must be > 0");
+  void* p = nullptr;
+  hipError_t e = hipHostMalloc(&p, ma_pinned_bytes(bytes, MA_PINNED_PAGE), hipHostMallocPortable);
+  if (e != hipSuccess) return fail_hip(e, "hipHostMalloc");
+  *host_ptr_out = p;
+  return MA_OK;
+}
+
+int ma_pinned_free(void* host_ptr) {
+  if (!host_ptr) return fail(MA_ERR_NULL, "host_ptr is NULL");
+  hipError_t e = hipHostFree(host_ptr);
+  if (e != hipSuccess) return fail_hip(e, "hipHostFree");
+  return MA_OK;
+}
+
 size_t ma_workspace_bytes(void) { return size_t(ma::kMaxNormBlocks) * sizeof(ma::NormPartial); }
 
 float ma_clip_coef(double sumsq, float max_norm) {
