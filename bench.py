@@ -13,7 +13,8 @@ bounded sample of the same workload.
 Workloads: llama3_8b (default; 290-tensor Llama-3-8B-shaped list, 8.03e9 elements, bf16
 gradients, clip 1.0; --layout tensor|streams), flat_1e8, fp16_5e7, c1, qwen14b_4sub (12.57e9 elements as 4 flat
 sub-groups streamed on one stream); rows beyond the basic step at the 8B element count:
-bf16_states_8b (p/m/v held in bf16, truncating stores, 14 B/param), accumulate_8b (4 bf16
+fp32grad_8b (the 8B list with fp32 gradients: the accumulated flat buffer of Sec. III-C as input,
+4 + 30 B/param), bf16_states_8b (p/m/v held in bf16, truncating stores, 14 B/param), accumulate_8b (4 bf16
 micro-batch gradients into the fp32 flat buffer, 6 / 10 B/param), auto_fp16_8b (fp16 gradients,
 loss scale, update number and gate all read on the device).
 """
@@ -101,20 +102,24 @@ class Workload:
         self.events = []
         self.step_bytes = STEP_BYTES_PER_PARAM
         self.kernel_label = "AdamW update (+ low-precision copy)"
-        if name == "llama3_8b":
+        if name in ("llama3_8b", "fp32grad_8b"):
             cfg = synth.FlatConfig(name, 0, seed=3, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
+            if name == "fp32grad_8b":      # the accumulated fp32 flat gradient buffer as the step's input
+                cfg.gdt = "f32"
+                self.step_bytes = 30.0      # read p, m, v (12) + g (4), write p, m, v (12) + p_lp (2)
             self.cfg = cfg
             self.layout = layout
             shapes = synth.llama3_8b_shapes()
             self.state = synth.make_list(shapes, cfg, device="cuda", layout=layout,
-                                         arena=place(synth.list_state_bytes(shapes, layout),
-                                                     synth.list_traffic(shapes, layout)))
+                                         arena=place(synth.list_state_bytes(shapes, layout, gdt=cfg.gdt),
+                                                     synth.list_traffic(shapes, layout, gdt=cfg.gdt)))
             self.plan = ma.MultiPlan(self.state.p, self.state.m, self.state.v, self.state.g,
                                      self.state.p_lp)
             self.n = self.plan.total
             self.kind = "multi"
-            self.desc = ("290-tensor Llama-3-8B-shaped list, %d elements, fp32 p/m/v, bf16 grads "
-                         "~N(0,1e-3), clip 1.0; layout '%s', placement '%s'" % (self.n, layout, self.placement))
+            self.desc = ("290-tensor Llama-3-8B-shaped list, %d elements, fp32 p/m/v, %s grads "
+                         "~N(0,1e-3), clip 1.0; layout '%s', placement '%s'"
+                         % (self.n, cfg.gdt, layout, self.placement))
         elif name == "qwen14b_4sub":
             cfg = synth.FlatConfig(name, 0, seed=4, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
             self.cfg = cfg
@@ -292,7 +297,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="llama3_8b",
-                    choices=["llama3_8b", "flat_1e8", "fp16_5e7", "c1", "qwen14b_4sub",
+                    choices=["llama3_8b", "fp32grad_8b", "flat_1e8", "fp16_5e7", "c1", "qwen14b_4sub",
                              "bf16_states_8b", "accumulate_8b", "auto_fp16_8b"])
     ap.add_argument("--layout", default="streams", choices=["streams", "tensor"],
                     help="llama3_8b only: how the list's buffers lie in the state: 'streams' = five flat "
@@ -364,7 +369,7 @@ def main():
     launches = {"sub": 4, "accum": wl.micro - 1 if wl.kind == "accum" else 1}.get(wl.kind, 1)
     passes = launches if wl.kind == "accum" else 1          # times the second phase sweeps all n elements
     achieved = wl.step_bytes * wl.n * passes / (rest_ms * 1e-3) / 1e9
-    gdt_bytes = 2.0
+    gdt_bytes = 4.0 if wl.cfg.gdt == "f32" else 2.0
     if wl.kind == "accum":
         first = {"kernel": "first micro-batch (overwrite)", "avg_ms": first_ms, "bytes_per_param": 6.0,
                  "achieved": 6.0 * wl.n / (first_ms * 1e-3) / 1e9}

@@ -15,7 +15,8 @@ from typing import List, Optional, Tuple
 
 import torch
 
-_TORCH_LP = {"bf16": torch.bfloat16, "f16": torch.float16}
+_TORCH_LP = {"bf16": torch.bfloat16, "f16": torch.float16, "f32": torch.float32}
+_BYTES = {"bf16": 2, "f16": 2, "f32": 4}
 
 # 16-bit non-finite patterns planted by the overflow variants: +inf, -inf, quiet NaN,
 # signalling-NaN pattern, negative NaN.
@@ -115,8 +116,8 @@ def plant_nonfinite(g: torch.Tensor, gdt: str, count: int, seed: int) -> List[in
 ARENA_ALIGN = 2 << 20   # every buffer of a state starts on a 2 MiB boundary of the arena
 
 
-def _flat_layout(n: int):
-    sizes = [4 * n, 4 * n, 4 * n, 2 * n, 2 * n]
+def _flat_layout(n: int, gdt: str = "bf16"):
+    sizes = [4 * n, 4 * n, 4 * n, _BYTES[gdt] * n, 2 * n]
     offs, total = [], 0
     for sz in sizes:
         offs.append(total)
@@ -124,15 +125,15 @@ def _flat_layout(n: int):
     return offs, sizes, max(total, 1)
 
 
-def flat_state_bytes(n: int) -> int:
-    """Bytes carve_state needs for n elements."""
-    return _flat_layout(n)[2]
+def flat_state_bytes(n: int, gdt: str = "bf16") -> int:
+    """Bytes carve_state needs for n elements (gradient dtype gdt: "bf16", "f16" or "f32")."""
+    return _flat_layout(n, gdt)[2]
 
 
-def flat_traffic(n: int):
+def flat_traffic(n: int, gdt: str = "bf16"):
     """(bytes, bytes moved per byte stored) of the five pieces in address order: p, m, v are read
     and written by the update, the gradient is only read, the parameter copy only written."""
-    offs, _, total = _flat_layout(n)
+    offs, _, total = _flat_layout(n, gdt)
     ends = offs[1:] + [total]
     return [(e - o, w) for o, e, w in zip(offs, ends, (2.0, 2.0, 2.0, 1.0, 1.0))]
 
@@ -145,7 +146,7 @@ def carve_state(n: int, gdt: str, pdt: str, device: str, arena: Optional[torch.T
     makes that reproducible from process to process).  `arena`: an existing uint8 device buffer
     of at least flat_state_bytes(n) bytes to cut from, instead of a new allocation.
     """
-    offs, sizes, total = _flat_layout(n)
+    offs, sizes, total = _flat_layout(n, gdt)
     if arena is None:
         arena = torch.empty(total, dtype=torch.uint8, device=device)
     elif arena.dtype != torch.uint8 or arena.numel() < total:
@@ -255,8 +256,8 @@ def _list_offsets(shapes, align_elems: int):
     return offs, total
 
 
-def _tensor_places(shapes):
-    elem = (4, 4, 4, 2, 2)
+def _tensor_places(shapes, gdt: str = "bf16"):
+    elem = (4, 4, 4, _BYTES[gdt], 2)
     places, total = [], 0
     for _, numel in shapes:
         row = []
@@ -269,17 +270,19 @@ def _tensor_places(shapes):
     return places, max(total, 1)
 
 
-def list_state_bytes(shapes: List[Tuple[str, int]], layout: str = "streams", align_elems: int = 64) -> int:
-    """Bytes make_list needs for this list and layout."""
+def list_state_bytes(shapes: List[Tuple[str, int]], layout: str = "streams", align_elems: int = 64,
+                     gdt: str = "bf16") -> int:
+    """Bytes make_list needs for this list, layout and gradient dtype."""
     if layout == "streams":
-        return flat_state_bytes(_list_offsets(shapes, align_elems)[1])
-    return _tensor_places(shapes)[1]
+        return flat_state_bytes(_list_offsets(shapes, align_elems)[1], gdt)
+    return _tensor_places(shapes, gdt)[1]
 
 
-def list_traffic(shapes: List[Tuple[str, int]], layout: str = "streams", align_elems: int = 64):
+def list_traffic(shapes: List[Tuple[str, int]], layout: str = "streams", align_elems: int = 64,
+                 gdt: str = "bf16"):
     """Traffic weights of the list's pieces in address order (None: uniform)."""
     if layout == "streams":
-        return flat_traffic(_list_offsets(shapes, align_elems)[1])
+        return flat_traffic(_list_offsets(shapes, align_elems)[1], gdt)
     return None
 
 
@@ -306,7 +309,7 @@ def make_list(shapes: List[Tuple[str, int]], cfg: FlatConfig, device: str = "cpu
     if layout != "tensor":
         raise ValueError("layout must be 'streams' or 'tensor'")
     dts = (torch.float32, torch.float32, torch.float32, _TORCH_LP[cfg.gdt], _TORCH_LP[cfg.pdt])
-    places, total = _tensor_places(shapes)
+    places, total = _tensor_places(shapes, cfg.gdt)
     if arena is None:
         arena = torch.empty(total, dtype=torch.uint8, device=device)
     elif arena.dtype != torch.uint8 or arena.numel() < total:
@@ -335,6 +338,9 @@ def make_list(shapes: List[Tuple[str, int]], cfg: FlatConfig, device: str = "cpu
 
 
 def bits16(t: torch.Tensor):
-    """Raw 16-bit patterns of a bf16/fp16 tensor as a numpy uint16 array (host copy)."""
+    """Raw 16-bit patterns of a bf16/fp16 tensor as a numpy uint16 array (host copy); an fp32 tensor
+    comes back as a float32 array."""
     import numpy as np
+    if t.dtype == torch.float32:
+        return t.detach().cpu().contiguous().numpy().copy()
     return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16).copy()
