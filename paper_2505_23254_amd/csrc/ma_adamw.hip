@@ -289,7 +289,14 @@ __device__ __forceinline__ void tile_load(Tile<SDT, GDT>& t, const Item& it) {
   }
 }
 
-template <int SDT, int GDT, int PDT>
+// PACE: a pause (s_sleep units) between the computation of a tile and its stores.  Measured on
+// MI355X with one block per CU, the 1:1 read/write mix of fp32 states sustains more when every CU
+// holds back a little (about 0.8 us of a 4.6 us tile period): 8B-shaped list 6.25-6.28 TB/s
+// without a pause, 6.32 at 24 units, 6.35 at 28, 6.38 at 32, 6.36 at 36, 6.34 at 40; a flat
+// 3.7e9-element sub-group 6.27 / 6.37 / 6.41 / 6.40 / 6.38 / 6.36.  The same pause before the
+// tile's loads does as well on large inputs and 1-3 % worse on small ones; split over both places,
+// or spread between the groups of a tile, it is worse.  bf16 states do not react to it.
+template <int SDT, int GDT, int PDT, int PACE>
 __device__ __forceinline__ void tile_finish(Tile<SDT, GDT>& t, const Item& it, const StepScalars& s) {
   constexpr int kUnroll = StateIO<SDT>::kUnroll;
   constexpr uint64_t kChunkGroups = uint64_t(kBlock) * kUnroll;
@@ -298,6 +305,7 @@ __device__ __forceinline__ void tile_finish(Tile<SDT, GDT>& t, const Item& it, c
   u32x2 L[kUnroll];
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) step_group<SDT, GDT, PDT>(s, t.P[u], t.M[u], t.V[u], t.G[u], L[u]);
+  if constexpr (PACE > 0) __builtin_amdgcn_s_sleep(PACE);
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
     const uint64_t gi = g0 + uint64_t(u) * kBlock;
@@ -308,11 +316,11 @@ __device__ __forceinline__ void tile_finish(Tile<SDT, GDT>& t, const Item& it, c
   }
 }
 
-template <int SDT, int GDT, int PDT>
+template <int SDT, int GDT, int PDT, int PACE>
 __device__ __forceinline__ void item_finish(bool tile, Tile<SDT, GDT>& t, const Item& it,
                                             const StepScalars& s) {
   if (tile) {
-    tile_finish<SDT, GDT, PDT>(t, it, s);
+    tile_finish<SDT, GDT, PDT, PACE>(t, it, s);
   } else {
     step_chunk<SDT, GDT, PDT>(s, it);
   }
@@ -327,7 +335,7 @@ __device__ __forceinline__ void item_finish(bool tile, Tile<SDT, GDT>& t, const 
 // form: a variant with straight-line runs of tiles, whose stores go out while the prefetch is
 // still in flight, was 1 % slower (more reads and writes in flight at once lower the bandwidth the
 // memory system sustains), and an explicit drain before the stores changed nothing.
-template <int SDT, int GDT, int PDT, class Locate>
+template <int SDT, int GDT, int PDT, int PACE, class Locate>
 __device__ __forceinline__ void step_pipeline(const StepScalars& s, uint64_t chunks, Locate locate) {
   WorkIter<MA_STEP_MAP> w(chunks);
   if (w.c >= w.end) return;
@@ -345,7 +353,7 @@ __device__ __forceinline__ void step_pipeline(const StepScalars& s, uint64_t chu
       fb = item_is_tile<SDT>(ib);
       if (fb) tile_load<SDT, GDT>(tb, ib);
     }
-    item_finish<SDT, GDT, PDT>(fa, ta, ia, s);
+    item_finish<SDT, GDT, PDT, PACE>(fa, ta, ia, s);
     if (!more) break;
     w.c = next;
     // B is current; start A
@@ -356,7 +364,7 @@ __device__ __forceinline__ void step_pipeline(const StepScalars& s, uint64_t chu
       fa = item_is_tile<SDT>(ia);
       if (fa) tile_load<SDT, GDT>(ta, ia);
     }
-    item_finish<SDT, GDT, PDT>(fb, tb, ib, s);
+    item_finish<SDT, GDT, PDT, PACE>(fb, tb, ib, s);
     if (!more) break;
     w.c = next;
   }
@@ -400,7 +408,7 @@ template <int SDT, int GDT, int PDT>
 __global__ __launch_bounds__(kBlock) void step_flat_kernel(Desc row, uint64_t chunks, StepScalars s,
                                                           StepControl ctl) {
   if (!prepare_step(ctl, s)) return;
-  step_pipeline<SDT, GDT, PDT>(s, chunks, [&](uint64_t c, Item& it) {
+  step_pipeline<SDT, GDT, PDT, step_pace(SDT, false)>(s, chunks, [&](uint64_t c, Item& it) {
     it.p = row.p;
     it.m = row.m;
     it.v = row.v;
@@ -418,29 +426,40 @@ __global__ __launch_bounds__(kBlock) void step_multi_kernel(const Desc* __restri
                                                            uint32_t rows, uint64_t chunks,
                                                            StepScalars s, StepControl ctl) {
   if (!prepare_step(ctl, s)) return;
-  uint32_t r = 0;  // rows are visited in increasing order: the last hit bounds the next search
-  step_pipeline<SDT, GDT, PDT>(s, chunks, [&](uint64_t c, Item& it) {
-    // largest row whose first work item is <= c (uniform => scalar unit)
-    uint32_t lo = r, hi = rows;
-    while (hi - lo > 1) {
-      const uint32_t mid = lo + (hi - lo) / 2;
-      if (table[mid].step_chunk0 <= c) {
-        lo = mid;
-      } else {
-        hi = mid;
+  // A block's work items advance in steps much smaller than a typical tensor, so the row of the
+  // previous item is kept (in scalar registers) together with the range of items it covers, and
+  // the table is searched only when an item falls outside that range.  Rows are visited in
+  // increasing order: the last hit bounds the search from below.
+  uint32_t r = 0;
+  uint64_t row_first = 1, row_end = 0;  // empty range: the first item always searches
+  Item row{};
+  step_pipeline<SDT, GDT, PDT, step_pace(SDT, true)>(s, chunks, [&](uint64_t c, Item& it) {
+    if (c < row_first || c >= row_end) {
+      // largest row whose first work item is <= c (uniform => scalar unit)
+      uint32_t lo = r, hi = rows;
+      while (hi - lo > 1) {
+        const uint32_t mid = lo + (hi - lo) / 2;
+        if (table[mid].step_chunk0 <= c) {
+          lo = mid;
+        } else {
+          hi = mid;
+        }
       }
+      r = lo;
+      const Desc* d = table + r;
+      row.p = d->p;
+      row.m = d->m;
+      row.v = d->v;
+      row.g = d->g;
+      row.lp = d->lp;
+      row.n = d->n;
+      row.head = d->step_head;
+      row.vec = d->step_vec;
+      row_first = d->step_chunk0;
+      row_end = (r + 1 < rows) ? table[r + 1].step_chunk0 : chunks;
     }
-    r = lo;
-    const Desc* d = table + r;
-    it.p = d->p;
-    it.m = d->m;
-    it.v = d->v;
-    it.g = d->g;
-    it.lp = d->lp;
-    it.n = d->n;
-    it.head = d->step_head;
-    it.vec = d->step_vec;
-    it.lc = c - d->step_chunk0;
+    it = row;
+    it.lc = c - row_first;
   });
 }
 

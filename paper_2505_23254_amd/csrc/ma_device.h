@@ -38,6 +38,15 @@ constexpr int kNoLp = 3;  // update kernel variant that writes no low-precision 
 #ifndef MA_STEP_UNROLL_BF16
 #define MA_STEP_UNROLL_BF16 4  // 8-element groups per lane and tile when p, m, v are held in bf16
 #endif
+#ifndef MA_STEP_PACE_MULTI
+#define MA_STEP_PACE_MULTI 32  // s_sleep units (64 clocks each) before a tile's stores: multi-tensor kernel, fp32 states
+#endif
+#ifndef MA_STEP_PACE_FLAT
+#define MA_STEP_PACE_FLAT 28  // the same for the flat kernel
+#endif
+#ifndef MA_STEP_PACE_BF16
+#define MA_STEP_PACE_BF16 0  // the same for states held in bf16 (either kernel)
+#endif
 #ifndef MA_STEP_MAP
 #define MA_STEP_MAP 2  // work-item assignment of the update kernel (see WorkIter)
 #endif
@@ -51,6 +60,9 @@ constexpr uint64_t kNormChunkBytes = uint64_t(kBlock) * 16 * kNormUnroll;  // pe
 __host__ __device__ constexpr int step_group_elems(int sdt) { return sdt == kF32 ? 4 : 8; }
 __host__ __device__ constexpr int step_unroll(int sdt) {
   return sdt == kF32 ? MA_STEP_UNROLL : MA_STEP_UNROLL_BF16;
+}
+__host__ __device__ constexpr int step_pace(int sdt, bool multi) {
+  return sdt != kF32 ? MA_STEP_PACE_BF16 : multi ? MA_STEP_PACE_MULTI : MA_STEP_PACE_FLAT;
 }
 // elements per work item of the update kernel
 __host__ __device__ constexpr uint64_t step_chunk_elems(int sdt) {
