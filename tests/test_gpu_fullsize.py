@@ -1,10 +1,11 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
 
 Flat configurations up to 10^8 elements are compared element by element.  The 8B-shaped list
-(8.03e9 elements), the 14B-class list as 4 streamed sub-groups (12.57e9) and a flat sub-group
-just beyond 2^31 elements are compared on samples the oracle can compute one by one -- the first
-and last 65,536 elements of every tensor, both sides of every sub-group cut, and seeded random
-blocks -- while the overflow flag and the sum of squares are checked over ALL elements.
+(8.03e9 elements), the 14B-class list as 4 streamed sub-groups (12.57e9), a flat sub-group just
+beyond 2^31 elements, and the 8.03e9-element bf16-state and accumulation workloads are compared on
+samples the oracle can compute one by one -- the first and last 65,536 elements of every tensor,
+both sides of every sub-group cut and of element 2^32, and seeded random blocks -- while the
+overflow flag and the sum of squares are checked over ALL elements.
 """
 import numpy as np
 import pytest
@@ -273,3 +274,86 @@ def test_flat_sub_group_beyond_2_to_31():
     fl.g.view(torch.int16)[n - 1] = 0x7C00
     ma.overflow_norm(fl.g, 512.0, res, ws, index=1)
     assert ma.read_result(res, 1)[0] is True
+
+
+N_8B = 8_030_257_152
+
+
+def _random_ranges(n, seed, count):
+    rng = np.random.default_rng(seed)
+    r = [(0, EDGE), (n - EDGE, n), ((1 << 32) - EDGE, (1 << 32) + EDGE)]
+    r += [(a, a + EDGE) for a in rng.integers(0, n - EDGE, count).tolist()]
+    return _merge(r, n)
+
+
+def test_bf16_states_8b_sampled():
+    """The bf16-state benchmark workload: one flat sub-group of 8,030,257,152 elements with p, m, v
+    held in bf16 (Extended Experiments), scan then gated truncating update; sampled blocks bit-exact,
+    flag and sum of squares over all elements."""
+    _need_gib(80)
+    n = N_8B
+    cfg = synth.FlatConfig("bf16_states_8b", n, seed=5, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(cfg.seed)
+    p, m, v, g = (torch.empty(n, dtype=torch.bfloat16, device="cuda") for _ in range(4))
+    for t, std in ((p, cfg.p_std), (m, cfg.m_std), (v, cfg.v_std), (g, cfg.g_std)):
+        synth._fill_grad(t, std, 1.0, gen)
+    v.abs_()
+    ranges = _random_ranges(n, 29, 900)
+    rp, rm, rv = (synth.bits16(_gather(t, ranges)) for t in (p, m, v))
+    g_s = host_grad(_gather(g, ranges))
+    ov_ref, ss_ref = _oracle_norm_all(g, "bf16", 1.0)
+    c_ref = oracle.clip_coef(ss_ref, 1.0)
+    assert not ov_ref and 0.005 < c_ref < 0.02
+    oracle.adamw_step_bf16(rp, rm, rv, g_s, "bf16", oracle_hyper(cfg), 100, 1.0, float(c_ref), nthreads=THREADS)
+    ws, res = ma.workspace(), ma.new_result()
+    ma.overflow_norm(g, 1.0, res, ws)
+    ma.adamw_step_bf16_gated(p, m, v, g, _hyper(cfg), 100, 1.0, res, 1.0)
+    ov, ss = ma.read_result(res)
+    assert not ov and abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref
+    assert np.float32(ma.clip_coef(ss, 1.0)) == c_ref
+    for name, t, ref in (("p", p, rp), ("m", m, rm), ("v", v, rv)):
+        got = synth.bits16(_gather(t, ranges))
+        assert np.array_equal(got, ref), "%s: %d of %d sampled patterns differ" % (name, (got != ref).sum(), ref.size)
+    assert np.array_equal(host_grad(_gather(g, ranges)), g_s)        # gradients are read-only
+    # an overflow anywhere skips the whole sub-group
+    sums = [int(t.view(torch.int16).sum(dtype=torch.int64)) for t in (p, m, v)]
+    g.view(torch.int16)[n - 3] = 0x7F80
+    ma.overflow_norm(g, 1.0, res, ws)
+    ma.adamw_step_bf16_gated(p, m, v, g, _hyper(cfg), 101, 1.0, res, 1.0)
+    assert ma.read_result(res)[0] is True
+    assert [int(t.view(torch.int16).sum(dtype=torch.int64)) for t in (p, m, v)] == sums
+
+
+def test_accumulate_8b_sampled():
+    """The accumulation benchmark workload: three bf16 micro-batch gradients of 8,030,257,152 elements
+    into the fp32 flat buffer (overwrite, add, add fused with the scan); sampled blocks bit-exact,
+    flag and sum of squares against the oracle's scan of the whole accumulated buffer."""
+    _need_gib(60)
+    n = N_8B
+    S = 1024.0
+    acc = torch.empty(n, dtype=torch.float32, device="cuda")
+    acc[:EDGE] = float("nan")                                # whatever the buffer held is overwritten
+    g = torch.empty(n, dtype=torch.bfloat16, device="cuda")
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(31)
+    ranges = _random_ranges(n, 37, 900)
+    ref = np.zeros(sum(b - a for a, b in ranges), np.float32)
+    ws, res = ma.workspace(), ma.new_result()
+    for k in range(3):
+        synth._fill_grad(g, 1e-3, S, gen)
+        oracle.grad_accumulate(ref, host_grad(_gather(g, ranges)), "bf16", first=(k == 0))
+        if k < 2:
+            ma.grad_accumulate(acc, g, first=(k == 0))
+        else:
+            ma.grad_accumulate_scan(acc, g, False, S, res, ws)
+    assert np.array_equal(host_f32(_gather(acc, ranges)).view(np.uint32), ref.view(np.uint32))
+    ov_ref, ss_ref = _oracle_norm_all(acc, "f32", S, piece=1 << 27)
+    ov, ss = ma.read_result(res)
+    assert not ov and not ov_ref
+    assert abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref
+    assert abs(ss / n - 3e-6) < 1e-8                         # three N(0, 1e-3) draws: variance 3e-6 each
+    # a NaN arriving with the next micro-batch is seen by the fused scan
+    g.view(torch.int16)[n - 1] = 0x7FC1
+    ma.grad_accumulate_scan(acc, g, False, S, res, ws)
+    assert ma.read_result(res)[0] is True
