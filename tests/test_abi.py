@@ -292,3 +292,40 @@ def test_region_window_placement():
     assert s >= 0 and e <= 283 * G
     with pytest.raises(ValueError):
         a.window(284 * G)
+
+
+def test_header_is_plain_c_and_layouts_match_the_binding(tmp_path):
+    """include/ma.h compiles as C99 and as C++ with every warning an error, and each struct the
+    binding mirrors has the size and field offsets the C compiler gives it."""
+    import subprocess
+    mirrors = {"ma_hyper": ma.Hyper, "ma_tensor": ma.Tensor, "ma_tensor_bf16": ma.TensorBF16,
+               "ma_scaler_config": ma.ScalerConfig, "ma_model_dims": ma.ModelDims,
+               "ma_pool_layout": ma.PoolLayout, "ma_multi_plan": ma.MultiPlanStruct}
+    lines = ['#include "ma.h"', "#include <stdio.h>", "#include <stddef.h>", "int main(void) {"]
+    for cname, cls in mirrors.items():
+        lines.append('  printf("%s size %%zu\\n", sizeof(%s));' % (cname, cname))
+        for field, _ in cls._fields_:
+            lines.append('  printf("%s %s %%zu\\n", offsetof(%s, %s));' % (cname, field, cname, field))
+    for cname in ("ma_norm_result", "ma_scaler_state"):
+        lines.append('  printf("%s size %%zu\\n", sizeof(%s));' % (cname, cname))
+    lines += ["  return 0;", "}"]
+    src = tmp_path / "layout.c"
+    src.write_text("\n".join(lines) + "\n")
+    inc = os.path.join(ROOT, "include")
+    exe = tmp_path / "layout"
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Wpedantic", "-Werror", "-I", inc, str(src), "-o", str(exe)],
+                   check=True, capture_output=True)
+    cpp = tmp_path / "layout.cpp"
+    cpp.write_text(src.read_text())
+    subprocess.run(["g++", "-std=c++11", "-Wall", "-Wextra", "-Wpedantic", "-Werror", "-fsyntax-only", "-I", inc, str(cpp)],
+                   check=True, capture_output=True)
+    got = {}
+    for line in subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n"):
+        if line:
+            a, b, c = line.split()
+            got[(a, b)] = int(c)
+    for cname, cls in mirrors.items():
+        assert got[(cname, "size")] == ctypes.sizeof(cls), cname
+        for field, _ in cls._fields_:
+            assert got[(cname, field)] == getattr(cls, field).offset, (cname, field)
+    assert got[("ma_norm_result", "size")] == 16 and got[("ma_scaler_state", "size")] == 24
