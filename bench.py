@@ -42,8 +42,8 @@ SCAN_BYTES_PER_PARAM = 2.0     # scan kernel: read g
 # profiles/hbm_traffic_counters__llama3_8b.txt).  Valid only for the kernel sources they were taken
 # with: when the digest of the kernel sources differs, the figure is reported as null.
 MEASURED_TRAFFIC = {
-    "kernel_sha256": "9add4e7aacb6c7971321ad3ccb6d7bb544f1ee17d3aeabf3ee10b4badd8714a0",
-    "llama3_8b": 224846347717,
+    "kernel_sha256": "94ce2648c45b6d33c4a75e2c6fed9fb10da201f86b613c81fd73d24918b93933",
+    "llama3_8b": 224846474677,
 }
 
 

@@ -24,8 +24,9 @@ constexpr int kNoLp = 3;  // update kernel variant that writes no low-precision 
 
 // Launch shape, chosen by measurement on MI355X (256 CUs, 8 XCDs).  The update kernel moves a 1:1
 // read/write mix and is fastest with FEW resident waves that each keep a deep tile in flight (one
-// block per CU, four 4-element groups per lane, next tile prefetched): a small moving window keeps
-// DRAM pages open and read/write turnarounds rare.  The read-only scan kernel prefers more waves.
+// block per CU, four 4-element groups per lane, next tile prefetched) and that pause briefly
+// before each tile's stores: more requests in flight than that lower the rate the memory system
+// sustains on this mix.  The read-only scan kernel prefers more waves.
 #ifndef MA_NORM_UNROLL
 #define MA_NORM_UNROLL 8  // 16-byte loads in flight per lane in the scan kernel
 #endif
@@ -36,7 +37,7 @@ constexpr int kNoLp = 3;  // update kernel variant that writes no low-precision 
 #define MA_NORM_MAP 0  // work-item assignment of the scan kernel (see WorkIter)
 #endif
 #ifndef MA_STEP_UNROLL_BF16
-#define MA_STEP_UNROLL_BF16 4  // 8-element groups per lane and tile when p, m, v are held in bf16
+#define MA_STEP_UNROLL_BF16 6  // 8-element groups per lane and tile when p, m, v are held in bf16
 #endif
 #ifndef MA_STEP_PACE_MULTI
 #define MA_STEP_PACE_MULTI 32  // s_sleep units (64 clocks each) before a tile's stores: multi-tensor kernel, fp32 states

@@ -12,7 +12,7 @@
 #define MA_STEP_BLOCKS_PER_CU 1  // persistent blocks per compute unit, update kernel
 #endif
 #ifndef MA_STEP_BLOCKS_PER_CU_BF16
-#define MA_STEP_BLOCKS_PER_CU_BF16 2  // the same for states held in bf16
+#define MA_STEP_BLOCKS_PER_CU_BF16 1  // the same for states held in bf16
 #endif
 
 namespace ma {
