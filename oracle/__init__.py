@@ -23,7 +23,9 @@ class Hyper(ctypes.Structure):
 
 
 def _load():
-    path = _build.build(force=False)
+    # MA_ORACLE_LIBRARY: an alternative build of the oracle.  tests/test_oracle_mutants.py points it
+    # at deliberately broken builds to show that the pins notice each planted mistake.
+    path = os.environ.get("MA_ORACLE_LIBRARY") or _build.build(force=False)
     lib = ctypes.CDLL(path)
     vp, sz, i32, i64, f32, f64 = (ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32,
                                   ctypes.c_int64, ctypes.c_float, ctypes.c_double)
