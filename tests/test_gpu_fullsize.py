@@ -357,3 +357,33 @@ def test_accumulate_8b_sampled():
     g.view(torch.int16)[n - 1] = 0x7FC1
     ma.grad_accumulate_scan(acc, g, False, S, res, ws)
     assert ma.read_result(res)[0] is True
+
+
+def test_flat_fp32_states_beyond_2_to_32():
+    """One flat call on 8,030,257,155 elements (element indices beyond 2^32, a ragged tail of three):
+    scan, gated update with fp16 gradients and an fp16 copy; sampled blocks on both sides of element
+    2^32, flag and sum over all elements."""
+    _need_gib(135)
+    n = N_8B + 3
+    cfg = synth.FlatConfig("flat8b", n, seed=8, m_std=1e-4, v_std=1e-8, step=12, gdt="f16", pdt="f16",
+                           loss_scale=4096.0, max_norm=1.0)
+    fl = synth.make_flat(cfg, device="cuda")
+    ranges = _random_ranges(n, 41, 500)
+    before = _sample_state(fl, ranges, "f16")
+    g_s = host_grad(_gather(fl.g, ranges))
+    ov_ref, ss_ref = _oracle_norm_all(fl.g, "f16", 4096.0)
+    c_ref = oracle.clip_coef(ss_ref, 1.0)
+    assert not ov_ref and c_ref < 0.02
+    before["lp"] = oracle.adamw_step(before["p"], before["m"], before["v"], g_s, "f16", "f16",
+                                     oracle_hyper(cfg), 12, 4096.0, float(c_ref), nthreads=THREADS)
+    ws, res = ma.workspace(), ma.new_result(2)
+    ma.overflow_norm(fl.g, 4096.0, res, ws)
+    ma.adamw_step_gated(fl.p, fl.m, fl.v, fl.g, fl.p_lp, _hyper(cfg), 12, 4096.0, res, 1.0)
+    ov, ss = ma.read_result(res)
+    assert not ov and abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref
+    assert np.float32(ma.clip_coef(ss, 1.0)) == c_ref
+    assert_state_close(_sample_state(fl, ranges, "f16"), before, "flat 8B + 3")
+    # a NaN just beyond element 2^32 is seen
+    fl.g.view(torch.int16)[(1 << 32) + 1] = 0x7E00
+    ma.overflow_norm(fl.g, 4096.0, res, ws, index=1)
+    assert ma.read_result(res, 1)[0] is True
