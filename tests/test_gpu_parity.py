@@ -398,3 +398,35 @@ def test_several_steps_track_the_oracle():
         ma.overflow_norm(st.g, 1.0, res, ws)
         ma.adamw_step_gated(st.p, st.m, st.v, st.g, st.p_lp, _hyper(cfg), t, 1.0, res, cfg.max_norm)
         assert_state_close(_host_state(st, "bf16"), ref, "step %d" % t)
+
+
+def test_two_sub_groups_on_two_streams():
+    """The library keeps no state of its own between calls: two sub-groups, each with its own
+    workspace and result slot, stepped concurrently on two non-default streams (three iterations,
+    calls interleaved) end exactly where the oracle puts each of them."""
+    sizes = (2_000_003, 1_500_001)
+    cfgs = [synth.FlatConfig("s%d" % k, n, seed=60 + k, gdt=("bf16", "f16")[k], m_std=1e-4, v_std=1e-8,
+                             step=10, loss_scale=(1.0, 1024.0)[k], max_norm=(0.02, 0.5)[k])
+            for k, n in enumerate(sizes)]
+    sts = [synth.make_flat(c, device="cuda") for c in cfgs]
+    refs = [_host_state(st, "bf16") for st in sts]
+    g_hosts = [host_grad(st.g) for st in sts]
+    for k, c in enumerate(cfgs):
+        for it in range(3):
+            ov, _, _ = oracle.optimizer_step(refs[k]["p"], refs[k]["m"], refs[k]["v"], g_hosts[k], c.gdt,
+                                             refs[k]["lp"], "bf16", oracle_hyper(c), 10 + it, c.loss_scale,
+                                             c.max_norm)
+            assert not ov
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    wss = [ma.workspace(), ma.workspace()]
+    ress = [ma.new_result(), ma.new_result()]
+    for it in range(3):
+        for k, (c, st) in enumerate(zip(cfgs, sts)):
+            ma.overflow_norm(st.g, c.loss_scale, ress[k], wss[k], stream=streams[k])
+        for k, (c, st) in enumerate(zip(cfgs, sts)):
+            ma.adamw_step_gated(st.p, st.m, st.v, st.g, st.p_lp, _hyper(c), 10 + it, c.loss_scale, ress[k],
+                                c.max_norm, stream=streams[k])
+    torch.cuda.synchronize()
+    for k, st in enumerate(sts):
+        assert_state_close(_host_state(st, "bf16"), refs[k], "stream %d" % k)
