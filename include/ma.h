@@ -270,7 +270,11 @@ int ma_adamw_step_auto(float* p32, float* m, float* v, const void* grad, ma_dtyp
 
 /* ---- multi-tensor variants (one launch over a whole tensor list) ------------------------------ */
 
-/* Bytes of device memory ma_multi_prepare needs for a list of `count` tensors. */
+/* Bytes of device memory ma_multi_prepare needs for a list of `count` tensors: one row per tensor
+ * and a 64-byte head of counters with which the blocks of an update launch share out the last part
+ * of the work.  The library writes the table in ma_multi_prepare and the head during every
+ * ma_multi_adamw_step* launch (which leaves it zeroed again); the caller never touches it.  As the
+ * update launches of one plan write the same tensors, they must not overlap in time anyway. */
 size_t ma_multi_table_bytes(size_t count);
 
 /* Validates list_host[0..count) (host array of device pointers; gradient dtype gdt, parameter

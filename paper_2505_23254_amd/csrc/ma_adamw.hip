@@ -326,6 +326,98 @@ __device__ __forceinline__ void item_finish(bool tile, Tile<SDT, GDT>& t, const 
   }
 }
 
+// ---- which work items a block takes ------------------------------------------------------------------
+// Every block first sweeps a fixed share.  A tensor list brings device memory for a few counters
+// (StepQueue), and then the last 1/2^MA_STEP_POOL_SHIFT of every XCD's share is not dealt out in
+// advance: a block that has finished its fixed share draws items from its own XCD's pool, then
+// from the other XCDs' pools, until all are empty.  Measured on MI355X the blocks of a launch do not
+// run at one speed (the odd-numbered XCDs end 0.8-1.6 % later than the even ones on equal shares,
+// and the blocks of one XCD spread by another 0.3 %); on equal fixed shares the early blocks idle
+// until the last one ends.  Each pool index is handed out exactly once (one atomic add per item,
+// by one lane, passed on through LDS), so every work item is still processed exactly once, by
+// whichever block gets there.  The two phases are separate loops: the fixed-share loop is the one
+// whose timing the pause of tile_finish is tuned to, and it stays as it is without pools.
+
+// Pool of XCD y for a launch of `chunks` items: [base, base + pool).
+__device__ __forceinline__ void step_pool_of(uint64_t chunks, uint32_t y, uint64_t& base, uint64_t& pool) {
+  const uint64_t per_xcd = (chunks + 7) / 8;
+  const uint64_t lo = uint64_t(y) * per_xcd;
+  const uint64_t hi = (lo + per_xcd < chunks) ? lo + per_xcd : chunks;
+  const uint64_t count = hi > lo ? hi - lo : 0;
+  pool = count >> MA_STEP_POOL_SHIFT;
+  base = hi - pool;
+}
+
+// The fixed share.  pools: leave the XCDs' pools out (the grid is then a multiple of 8 blocks).
+struct FixedItems {
+  uint64_t c, end, stride;
+  __device__ __forceinline__ FixedItems(uint64_t chunks, bool pools) {
+    const WorkIter<MA_STEP_MAP> w(chunks);
+    c = w.c;
+    end = w.end;
+    stride = w.stride;
+    if (pools) {
+      uint64_t base, pool;
+      step_pool_of(chunks, blockIdx.x & 7, base, pool);
+      end = base;
+    }
+  }
+  __device__ __forceinline__ bool next(uint64_t& out) {
+    if (c >= end) return false;
+    out = c;
+    c += stride;
+    return true;
+  }
+};
+
+// Items drawn from the pools, MA_STEP_DRAW consecutive ones per draw: a draw costs the block a
+// barrier, which lines up its four otherwise free-running waves.
+struct PoolItems {
+  StepQueue* q;
+  uint32_t* slot;  // two words of LDS
+  uint64_t chunks;
+  uint64_t cur = 0;  // next item of the current draw
+  uint32_t left = 0;  // items of the current draw not yet handed out
+  uint32_t x, visited = 0, parity = 0;
+
+  __device__ __forceinline__ PoolItems(uint64_t chunks_, StepQueue* q_, uint32_t* slot_)
+      : q(q_), slot(slot_), chunks(chunks_), x(blockIdx.x & 7) {}
+
+  __device__ __forceinline__ bool next(uint64_t& out) {
+    while (left == 0) {
+      if (visited >= 8) return false;
+      const uint32_t y = (x + visited) & 7;
+      uint64_t base, pool;
+      step_pool_of(chunks, y, base, pool);
+      if (threadIdx.x == 0) slot[parity] = atomicAdd(&q->next[y], uint32_t(MA_STEP_DRAW));
+      __syncthreads();
+      const uint32_t idx = __builtin_amdgcn_readfirstlane(slot[parity]);
+      parity ^= 1u;  // the next draw writes the other word: one barrier per draw is enough
+      if (idx < pool) {
+        const uint64_t rest = pool - idx;
+        left = rest < MA_STEP_DRAW ? uint32_t(rest) : uint32_t(MA_STEP_DRAW);
+        cur = base + idx;
+      } else {
+        ++visited;
+      }
+    }
+    out = cur++;
+    --left;
+    return true;
+  }
+
+  // Called once by every block after its last item: the last block to arrive clears the queue.
+  __device__ __forceinline__ void finish() {
+    if (threadIdx.x != 0) return;
+    __threadfence();
+    if (atomicAdd(&q->done, 1u) == gridDim.x - 1) {
+#pragma unroll
+      for (int y = 0; y < 8; ++y) atomicExch(&q->next[y], 0u);
+      atomicExch(&q->done, 0u);
+    }
+  }
+};
+
 // locate(c, item) fills `item` for global work item c (c is uniform across the block).
 //
 // Two register tiles alternate: the loads of the next item are issued, then the current item is
@@ -335,38 +427,36 @@ __device__ __forceinline__ void item_finish(bool tile, Tile<SDT, GDT>& t, const 
 // form: a variant with straight-line runs of tiles, whose stores go out while the prefetch is
 // still in flight, was 1 % slower (more reads and writes in flight at once lower the bandwidth the
 // memory system sustains), and an explicit drain before the stores changed nothing.
-template <int SDT, int GDT, int PDT, int PACE, class Locate>
-__device__ __forceinline__ void step_pipeline(const StepScalars& s, uint64_t chunks, Locate locate) {
-  WorkIter<MA_STEP_MAP> w(chunks);
-  if (w.c >= w.end) return;
+template <int SDT, int GDT, int PDT, int PACE, class Items, class Locate>
+__device__ __forceinline__ void step_pipeline(const StepScalars& s, Items& items, Locate locate) {
   Item ia, ib;
   Tile<SDT, GDT> ta, tb;
-  locate(w.c, ia);
-  bool fa = item_is_tile<SDT>(ia), fb = false;
-  if (fa) tile_load<SDT, GDT>(ta, ia);
-  for (;;) {
-    // A is current; start B
-    uint64_t next = w.c + w.stride;
-    bool more = next < w.end;
-    if (more) {
-      locate(next, ib);
-      fb = item_is_tile<SDT>(ib);
-      if (fb) tile_load<SDT, GDT>(tb, ib);
+  uint64_t c = 0;
+  bool fa = false, fb = false;
+  if (items.next(c)) {
+    locate(c, ia);
+    fa = item_is_tile<SDT>(ia);
+    if (fa) tile_load<SDT, GDT>(ta, ia);
+    for (;;) {
+      // A is current; start B
+      bool more = items.next(c);
+      if (more) {
+        locate(c, ib);
+        fb = item_is_tile<SDT>(ib);
+        if (fb) tile_load<SDT, GDT>(tb, ib);
+      }
+      item_finish<SDT, GDT, PDT, PACE>(fa, ta, ia, s);
+      if (!more) break;
+      // B is current; start A
+      more = items.next(c);
+      if (more) {
+        locate(c, ia);
+        fa = item_is_tile<SDT>(ia);
+        if (fa) tile_load<SDT, GDT>(ta, ia);
+      }
+      item_finish<SDT, GDT, PDT, PACE>(fb, tb, ib, s);
+      if (!more) break;
     }
-    item_finish<SDT, GDT, PDT, PACE>(fa, ta, ia, s);
-    if (!more) break;
-    w.c = next;
-    // B is current; start A
-    next = w.c + w.stride;
-    more = next < w.end;
-    if (more) {
-      locate(next, ia);
-      fa = item_is_tile<SDT>(ia);
-      if (fa) tile_load<SDT, GDT>(ta, ia);
-    }
-    item_finish<SDT, GDT, PDT, PACE>(fb, tb, ib, s);
-    if (!more) break;
-    w.c = next;
   }
 }
 
@@ -408,7 +498,8 @@ template <int SDT, int GDT, int PDT>
 __global__ __launch_bounds__(kBlock) void step_flat_kernel(Desc row, uint64_t chunks, StepScalars s,
                                                           StepControl ctl) {
   if (!prepare_step(ctl, s)) return;
-  step_pipeline<SDT, GDT, PDT, step_pace(SDT, false)>(s, chunks, [&](uint64_t c, Item& it) {
+  FixedItems items(chunks, false);
+  step_pipeline<SDT, GDT, PDT, step_pace(SDT, false)>(s, items, [&](uint64_t c, Item& it) {
     it.p = row.p;
     it.m = row.m;
     it.v = row.v;
@@ -424,19 +515,21 @@ __global__ __launch_bounds__(kBlock) void step_flat_kernel(Desc row, uint64_t ch
 template <int SDT, int GDT, int PDT>
 __global__ __launch_bounds__(kBlock) void step_multi_kernel(const Desc* __restrict__ table,
                                                            uint32_t rows, uint64_t chunks,
-                                                           StepScalars s, StepControl ctl) {
+                                                           StepScalars s, StepControl ctl,
+                                                           StepQueue* queue) {
+  __shared__ uint32_t draw_slot[2];
   if (!prepare_step(ctl, s)) return;
   // A block's work items advance in steps much smaller than a typical tensor, so the row of the
   // previous item is kept (in scalar registers) together with the range of items it covers, and
-  // the table is searched only when an item falls outside that range.  Rows are visited in
-  // increasing order: the last hit bounds the search from below.
+  // the table is searched only when an item falls outside that range.  While items increase the
+  // last hit bounds the search from below.
   uint32_t r = 0;
   uint64_t row_first = 1, row_end = 0;  // empty range: the first item always searches
   Item row{};
-  step_pipeline<SDT, GDT, PDT, step_pace(SDT, true)>(s, chunks, [&](uint64_t c, Item& it) {
+  auto locate = [&](uint64_t c, Item& it) {
     if (c < row_first || c >= row_end) {
       // largest row whose first work item is <= c (uniform => scalar unit)
-      uint32_t lo = r, hi = rows;
+      uint32_t lo = (c >= row_first) ? r : 0, hi = rows;
       while (hi - lo > 1) {
         const uint32_t mid = lo + (hi - lo) / 2;
         if (table[mid].step_chunk0 <= c) {
@@ -460,7 +553,14 @@ __global__ __launch_bounds__(kBlock) void step_multi_kernel(const Desc* __restri
     }
     it = row;
     it.lc = c - row_first;
-  });
+  };
+  FixedItems fixed(chunks, queue != nullptr);
+  step_pipeline<SDT, GDT, PDT, step_pace(SDT, true)>(s, fixed, locate);
+  if (queue != nullptr) {
+    PoolItems drawn(chunks, queue, draw_slot);
+    step_pipeline<SDT, GDT, PDT, step_pace(SDT, true)>(s, drawn, locate);
+    drawn.finish();
+  }
 }
 
 // ---- launcher ---------------------------------------------------------------------------------------
@@ -476,10 +576,13 @@ static int resident_blocks_per_cu(K kernel) {
   return nb;
 }
 
+// Fewest work items of a launch for which every XCD's pool holds at least one.
+constexpr uint64_t kMinItemsForPools = uint64_t(8) << MA_STEP_POOL_SHIFT;
+
 template <int SDT, int GDT, int PDT>
 static hipError_t launch_step_typed(const Desc* row_host, const Desc* table_dev, uint32_t rows,
                                     uint64_t chunks, const StepScalars& s, const StepControl& ctl,
-                                    int device_cus, hipStream_t stream) {
+                                    StepQueue* queue, int device_cus, hipStream_t stream) {
   // A persistent grid must be fully resident: blocks that wait for a slot would run alone at the
   // end.  So: no more blocks per compute unit than the kernel's occupancy allows.
   static const int occ_flat = resident_blocks_per_cu(step_flat_kernel<SDT, GDT, PDT>);
@@ -495,7 +598,9 @@ static hipError_t launch_step_typed(const Desc* row_host, const Desc* table_dev,
   if (row_host) {
     step_flat_kernel<SDT, GDT, PDT><<<grid, kBlock, 0, stream>>>(*row_host, chunks, s, ctl);
   } else {
-    step_multi_kernel<SDT, GDT, PDT><<<grid, kBlock, 0, stream>>>(table_dev, rows, chunks, s, ctl);
+    // pools of late items need whole XCD groups of blocks and something to put into them
+    StepQueue* q = ((grid & 7u) == 0 && chunks >= kMinItemsForPools) ? queue : nullptr;
+    step_multi_kernel<SDT, GDT, PDT><<<grid, kBlock, 0, stream>>>(table_dev, rows, chunks, s, ctl, q);
   }
   return hipGetLastError();
 }
@@ -503,15 +608,15 @@ static hipError_t launch_step_typed(const Desc* row_host, const Desc* table_dev,
 template <int SDT, int GDT>
 static hipError_t launch_step_g(int pdt, const Desc* row_host, const Desc* table_dev, uint32_t rows,
                                 uint64_t chunks, const StepScalars& s, const StepControl& ctl,
-                                int device_cus, hipStream_t stream) {
+                                StepQueue* queue, int device_cus, hipStream_t stream) {
   if constexpr (SDT != kF32) {
     // half-precision states: the parameter itself is the 16-bit copy
-    return launch_step_typed<SDT, GDT, kNoLp>(row_host, table_dev, rows, chunks, s, ctl, device_cus, stream);
+    return launch_step_typed<SDT, GDT, kNoLp>(row_host, table_dev, rows, chunks, s, ctl, queue, device_cus, stream);
   } else {
     switch (pdt) {
-      case kBF16: return launch_step_typed<SDT, GDT, kBF16>(row_host, table_dev, rows, chunks, s, ctl, device_cus, stream);
-      case kF16: return launch_step_typed<SDT, GDT, kF16>(row_host, table_dev, rows, chunks, s, ctl, device_cus, stream);
-      default: return launch_step_typed<SDT, GDT, kNoLp>(row_host, table_dev, rows, chunks, s, ctl, device_cus, stream);
+      case kBF16: return launch_step_typed<SDT, GDT, kBF16>(row_host, table_dev, rows, chunks, s, ctl, queue, device_cus, stream);
+      case kF16: return launch_step_typed<SDT, GDT, kF16>(row_host, table_dev, rows, chunks, s, ctl, queue, device_cus, stream);
+      default: return launch_step_typed<SDT, GDT, kNoLp>(row_host, table_dev, rows, chunks, s, ctl, queue, device_cus, stream);
     }
   }
 }
@@ -519,20 +624,21 @@ static hipError_t launch_step_g(int pdt, const Desc* row_host, const Desc* table
 template <int SDT>
 static hipError_t launch_step_s(int gdt, int pdt, const Desc* row_host, const Desc* table_dev,
                                 uint32_t rows, uint64_t chunks, const StepScalars& s,
-                                const StepControl& ctl, int device_cus, hipStream_t stream) {
+                                const StepControl& ctl, StepQueue* queue, int device_cus,
+                                hipStream_t stream) {
   switch (gdt) {
-    case kBF16: return launch_step_g<SDT, kBF16>(pdt, row_host, table_dev, rows, chunks, s, ctl, device_cus, stream);
-    case kF16: return launch_step_g<SDT, kF16>(pdt, row_host, table_dev, rows, chunks, s, ctl, device_cus, stream);
-    default: return launch_step_g<SDT, kF32>(pdt, row_host, table_dev, rows, chunks, s, ctl, device_cus, stream);
+    case kBF16: return launch_step_g<SDT, kBF16>(pdt, row_host, table_dev, rows, chunks, s, ctl, queue, device_cus, stream);
+    case kF16: return launch_step_g<SDT, kF16>(pdt, row_host, table_dev, rows, chunks, s, ctl, queue, device_cus, stream);
+    default: return launch_step_g<SDT, kF32>(pdt, row_host, table_dev, rows, chunks, s, ctl, queue, device_cus, stream);
   }
 }
 
 hipError_t launch_step(const Desc* row_host, const Desc* table_dev, uint32_t rows, uint64_t chunks,
                        int sdt, int gdt, int pdt, const StepScalars& s, const StepControl& ctl,
-                       int device_cus, hipStream_t stream) {
+                       StepQueue* queue, int device_cus, hipStream_t stream) {
   if (chunks == 0) return hipSuccess;
-  if (sdt == kBF16) return launch_step_s<kBF16>(gdt, pdt, row_host, table_dev, rows, chunks, s, ctl, device_cus, stream);
-  return launch_step_s<kF32>(gdt, pdt, row_host, table_dev, rows, chunks, s, ctl, device_cus, stream);
+  if (sdt == kBF16) return launch_step_s<kBF16>(gdt, pdt, row_host, table_dev, rows, chunks, s, ctl, queue, device_cus, stream);
+  return launch_step_s<kF32>(gdt, pdt, row_host, table_dev, rows, chunks, s, ctl, queue, device_cus, stream);
 }
 
 }  // namespace ma

@@ -184,6 +184,14 @@ int check_request(const StepRequest& q) {
   return MA_OK;
 }
 
+// A plan's device table: the update kernel's counters, then the rows.
+const ma::Desc* plan_rows(const ma_multi_plan* plan) {
+  return reinterpret_cast<const ma::Desc*>(static_cast<const char*>(plan->table_dev) + ma::kTableHeadBytes);
+}
+ma::StepQueue* plan_queue(const ma_multi_plan* plan) {
+  return static_cast<ma::StepQueue*>(const_cast<void*>(plan->table_dev));
+}
+
 int step_common(const ma::Desc* row, const ma_multi_plan* plan, uint64_t chunks, int sdt, int gdt,
                 int pdt, const StepRequest& q, void* stream) {
   int cus = 0;
@@ -199,9 +207,9 @@ int step_common(const ma::Desc* row, const ma_multi_plan* plan, uint64_t chunks,
   ctl.loss_scale = q.loss_scale;
   ctl.lr = q.hyper->lr;
   ctl.bias_correction = q.hyper->bias_correction;
-  hipError_t e = ma::launch_step(row, plan ? static_cast<const ma::Desc*>(plan->table_dev) : nullptr,
+  hipError_t e = ma::launch_step(row, plan ? plan_rows(plan) : nullptr,
                                  plan ? uint32_t(plan->entries) : 1u, chunks, sdt, gdt, pdt, s, ctl,
-                                 cus, static_cast<hipStream_t>(stream));
+                                 plan ? plan_queue(plan) : nullptr, cus, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return fail_hip(e, "update kernel launch");
   return MA_OK;
 }
@@ -248,7 +256,7 @@ int norm_common(const ma::Desc* row, const ma_multi_plan* plan, uint64_t chunks,
   int cus = 0;
   if (int rc = device_cus(&cus)) return rc;
   const double inv = scaler ? 1.0 : 1.0 / (double(loss_scale) * double(loss_scale));
-  hipError_t e = ma::launch_norm(row, plan ? static_cast<const ma::Desc*>(plan->table_dev) : nullptr,
+  hipError_t e = ma::launch_norm(row, plan ? plan_rows(plan) : nullptr,
                                  plan ? uint32_t(plan->entries) : 1u, chunks, gdt, inv,
                                  static_cast<const ma::ScalerState*>(scaler),
                                  static_cast<ma::NormPartial*>(ws),
@@ -312,10 +320,12 @@ int prepare_common(size_t count, ma_dtype gdt, int pdt, int sdt, void* table_dev
     elems += d.n;
     rows.push_back(d);
   }
-  if (!rows.empty()) {
+  {
+    // the counters (all zero), then the rows, in one copy
+    std::vector<char> image(ma::kTableHeadBytes + rows.size() * sizeof(ma::Desc), 0);
+    if (!rows.empty()) std::memcpy(image.data() + ma::kTableHeadBytes, rows.data(), rows.size() * sizeof(ma::Desc));
     hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t e = hipMemcpyAsync(table_dev, rows.data(), rows.size() * sizeof(ma::Desc),
-                                  hipMemcpyHostToDevice, s);
+    hipError_t e = hipMemcpyAsync(table_dev, image.data(), image.size(), hipMemcpyHostToDevice, s);
     if (e != hipSuccess) return fail_hip(e, "table upload");
     e = hipStreamSynchronize(s);
     if (e != hipSuccess) return fail_hip(e, "table upload (sync)");
@@ -579,7 +589,9 @@ int ma_scaler_update(ma_scaler_state* scaler_dev, const ma_norm_result* gate_dev
   return MA_OK;
 }
 
-size_t ma_multi_table_bytes(size_t count) { return (count ? count : 1) * sizeof(ma::Desc); }
+size_t ma_multi_table_bytes(size_t count) {
+  return ma::kTableHeadBytes + (count ? count : 1) * sizeof(ma::Desc);
+}
 
 int ma_multi_prepare(const ma_tensor* list_host, size_t count, ma_dtype gdt, ma_dtype pdt,
                      void* table_dev, size_t table_bytes, void* stream, ma_multi_plan* plan_out) {

@@ -48,6 +48,12 @@ constexpr int kNoLp = 3;  // update kernel variant that writes no low-precision 
 #ifndef MA_STEP_PACE_BF16
 #define MA_STEP_PACE_BF16 0  // the same for states held in bf16 (either kernel)
 #endif
+#ifndef MA_STEP_POOL_SHIFT
+#define MA_STEP_POOL_SHIFT 6  // tensor lists: the last 1/2^k of every XCD's share is handed out on demand
+#endif
+#ifndef MA_STEP_DRAW
+#define MA_STEP_DRAW 8  // work items a block takes from a pool at a time
+#endif
 #ifndef MA_STEP_MAP
 #define MA_STEP_MAP 2  // work-item assignment of the update kernel (see WorkIter)
 #endif
@@ -92,6 +98,16 @@ struct Desc {
   uint32_t pad;
 };
 static_assert(sizeof(Desc) == 80, "table row layout");
+
+// Head of a tensor list's device table: shared counters of the list's update launches.  next[y]
+// counts the late work items of XCD y's share that have been handed out, done the blocks that have
+// finished.  All zero between launches (the last block of a launch clears them).
+struct StepQueue {
+  uint32_t next[8];
+  uint32_t done;
+  uint32_t pad[7];
+};
+static_assert(sizeof(StepQueue) == 64, "table head layout");
 
 // Scalars of one AdamW step, each rounded to fp32 once on the host (or in the gated prologue).
 struct StepScalars {

@@ -34,10 +34,14 @@ hipError_t launch_norm_finalize(const NormPartial* partials, uint32_t count, int
 hipError_t launch_norm_combine(const NormResult* parts, uint32_t count, NormResult* out,
                                hipStream_t stream);
 
-// sdt: dtype of p, m, v (kF32, or kBF16 for states stored by truncation).
+// sdt: dtype of p, m, v (kF32, or kBF16 for states stored by truncation).  queue: the counters at
+// the head of a tensor list's table (null for a flat sub-group, which has no such memory).
 hipError_t launch_step(const Desc* row_host, const Desc* table_dev, uint32_t rows, uint64_t chunks,
                        int sdt, int gdt, int pdt, const StepScalars& s, const StepControl& ctl,
-                       int device_cus, hipStream_t stream);
+                       StepQueue* queue, int device_cus, hipStream_t stream);
+
+// A tensor list's device table: the counters, then one row per non-empty tensor.
+constexpr size_t kTableHeadBytes = sizeof(StepQueue);
 
 hipError_t launch_scaler_init(ScalerState* state, float scale, int64_t step, hipStream_t stream);
 hipError_t launch_scaler_update(ScalerState* state, const NormResult* gate, const ScalerConfig& cfg,

@@ -30,7 +30,8 @@ def test_every_declared_symbol_is_exported():
 def test_sizes_and_version():
     assert ma.version() >= 100
     assert ma.lib.ma_workspace_bytes() % 16 == 0 and ma.lib.ma_workspace_bytes() >= 4096 * 16
-    assert ma.lib.ma_multi_table_bytes(10) == 10 * ma.lib.ma_multi_table_bytes(1)
+    assert ma.lib.ma_multi_table_bytes(10) - ma.lib.ma_multi_table_bytes(1) == 9 * 80    # one 80-byte row per tensor
+    assert ma.lib.ma_multi_table_bytes(1) == 64 + 80                                     # after a 64-byte head
     assert ctypes.sizeof(ma.Hyper) == 24 and ctypes.sizeof(ma.Tensor) == 48
     assert ctypes.sizeof(ma.MultiPlanStruct) == 56
 
@@ -94,14 +95,14 @@ def test_multi_argument_errors():
     arr = (ma.Tensor * 2)(ma.Tensor(A, A, A, A, A, 8), ma.Tensor(A, A, A, A + 1, A, 8))
     plan = ma.MultiPlanStruct()
     prep = ma.lib.ma_multi_prepare
-    assert prep(arr, 2, ma.MA_BF16, ma.MA_BF16, A, 160, None, ctypes.byref(plan)) == ma.MA_ERR_ALIGN
+    assert prep(arr, 2, ma.MA_BF16, ma.MA_BF16, A, 224, None, ctypes.byref(plan)) == ma.MA_ERR_ALIGN
     assert b"tensor 1" in ma.lib.ma_last_error()
     assert prep(arr, 1, ma.MA_BF16, ma.MA_BF16, A, 10, None, ctypes.byref(plan)) == ma.MA_ERR_ARG
-    assert prep(arr, 0, ma.MA_BF16, ma.MA_BF16, A, 160, None, ctypes.byref(plan)) == ma.MA_ERR_ARG
-    assert prep(None, 1, ma.MA_BF16, ma.MA_BF16, A, 160, None, ctypes.byref(plan)) == ma.MA_ERR_NULL
-    assert prep(arr, 1, ma.MA_BF16, ma.MA_F32, A, 160, None, ctypes.byref(plan)) == ma.MA_ERR_DTYPE
+    assert prep(arr, 0, ma.MA_BF16, ma.MA_BF16, A, 224, None, ctypes.byref(plan)) == ma.MA_ERR_ARG
+    assert prep(None, 1, ma.MA_BF16, ma.MA_BF16, A, 224, None, ctypes.byref(plan)) == ma.MA_ERR_NULL
+    assert prep(arr, 1, ma.MA_BF16, ma.MA_F32, A, 224, None, ctypes.byref(plan)) == ma.MA_ERR_DTYPE
     mixed = (ma.Tensor * 2)(ma.Tensor(A, A, A, A, A, 8), ma.Tensor(A, A, A, A, None, 8))
-    assert prep(mixed, 2, ma.MA_BF16, ma.MA_BF16, A, 160, None, ctypes.byref(plan)) == ma.MA_ERR_ARG
+    assert prep(mixed, 2, ma.MA_BF16, ma.MA_BF16, A, 224, None, ctypes.byref(plan)) == ma.MA_ERR_ARG
     # a plan that did not come from ma_multi_prepare is refused
     assert ma.lib.ma_multi_adamw_step(ctypes.byref(plan), ctypes.byref(H), 1, 1.0, 1.0, None) == ma.MA_ERR_ARG
     assert ma.lib.ma_multi_overflow_norm(ctypes.byref(plan), 1.0, A, A, 1 << 20, None) == ma.MA_ERR_ARG
@@ -113,14 +114,14 @@ def test_multi_bf16_argument_errors():
     plan = ma.MultiPlanStruct()
     prep = ma.lib.ma_multi_prepare_bf16
     assert ctypes.sizeof(ma.TensorBF16) == 40
-    assert prep(arr, 2, ma.MA_BF16, A, 160, None, ctypes.byref(plan)) == ma.MA_ERR_ALIGN
+    assert prep(arr, 2, ma.MA_BF16, A, 224, None, ctypes.byref(plan)) == ma.MA_ERR_ALIGN
     assert b"tensor 1" in ma.lib.ma_last_error()
-    assert prep(arr, 1, 9, A, 160, None, ctypes.byref(plan)) == ma.MA_ERR_DTYPE
-    assert prep(None, 1, ma.MA_BF16, A, 160, None, ctypes.byref(plan)) == ma.MA_ERR_NULL
+    assert prep(arr, 1, 9, A, 224, None, ctypes.byref(plan)) == ma.MA_ERR_DTYPE
+    assert prep(None, 1, ma.MA_BF16, A, 224, None, ctypes.byref(plan)) == ma.MA_ERR_NULL
     assert prep(arr, 1, ma.MA_BF16, A, 8, None, ctypes.byref(plan)) == ma.MA_ERR_ARG
-    assert prep(arr, 1, ma.MA_BF16, A, 160, None, None) == ma.MA_ERR_NULL
+    assert prep(arr, 1, ma.MA_BF16, A, 224, None, None) == ma.MA_ERR_NULL
     nul = (ma.TensorBF16 * 1)(ma.TensorBF16(A, None, A, A, 8))
-    assert prep(nul, 1, ma.MA_BF16, A, 160, None, ctypes.byref(plan)) == ma.MA_ERR_NULL
+    assert prep(nul, 1, ma.MA_BF16, A, 224, None, ctypes.byref(plan)) == ma.MA_ERR_NULL
     # a plan with an unknown state dtype is refused
     good = ma.MultiPlanStruct(A, 1, 8, 1, 1, ma.MA_BF16, ma.MA_BF16, 0x4D415450, 7)
     assert ma.lib.ma_multi_adamw_step(ctypes.byref(good), ctypes.byref(H), 1, 1.0, 1.0, None) == ma.MA_ERR_ARG

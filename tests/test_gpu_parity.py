@@ -430,3 +430,45 @@ def test_two_sub_groups_on_two_streams():
     torch.cuda.synchronize()
     for k, st in enumerate(sts):
         assert_state_close(_host_state(st, "bf16"), refs[k], "stream %d" % k)
+
+
+def test_multi_list_repeated_launches_share_out_late_items():
+    """A 1/512-scale 8B-shaped list (about 4000 work items): large enough that the update kernel
+    hands the last part of every XCD's share out on demand.  Four iterations on one plan, the third
+    one skipped by an overflow: every element is updated exactly once per applied iteration,
+    whichever block took its work item, and the plan's counters are back at zero after every launch
+    (a stale counter would leave late items of the next launch undone)."""
+    shapes = synth.scaled_shapes(synth.llama3_8b_shapes(), 512, ragged=True)
+    cfg = synth.FlatConfig("t", 0, seed=77, m_std=1e-4, v_std=1e-8, step=100, max_norm=0.3)
+    ls = synth.make_list(shapes, cfg, device="cuda", align_elems=1)
+    refs = [dict(p=host_f32(ls.p[i]), m=host_f32(ls.m[i]), v=host_f32(ls.v[i]), lp=synth.bits16(ls.p_lp[i]),
+                 pdt="bf16") for i in range(len(shapes))]
+    g_hosts = [host_grad(g) for g in ls.g]
+    ss_ref = sum(oracle.overflow_norm(g, "bf16")[1] for g in g_hosts)
+    c_ref = oracle.clip_coef(ss_ref, float(np.float32(cfg.max_norm)))
+    plan = ma.MultiPlan(ls.p, ls.m, ls.v, ls.g, ls.p_lp)
+    assert plan.plan.step_chunks > 3000
+    ws, res = ma.workspace(), ma.new_result()
+    head = lambda: plan.table[:64].view(torch.int32).cpu().tolist()
+    assert head() == [0] * 16
+    step = 100
+    for it in range(4):
+        if it == 2:       # an overflow: the launch returns before any block touches the counters
+            keep = ls.g[3].view(torch.int16)[5].item()
+            ls.g[3].view(torch.int16)[5] = 0x7F80
+        ma.multi_overflow_norm(plan, 1.0, res, ws)
+        ma.multi_adamw_step_gated(plan, _hyper(cfg), step, 1.0, res, cfg.max_norm)
+        ov, ss = ma.read_result(res)
+        assert head() == [0] * 16, it
+        if it == 2:
+            assert ov
+            ls.g[3].view(torch.int16)[5] = keep
+            continue
+        assert not ov and abs(ss - ss_ref) <= 1e-12 * ss_ref
+        for r, g in zip(refs, g_hosts):
+            r["lp"] = oracle.adamw_step(r["p"], r["m"], r["v"], g, "bf16", "bf16", oracle_hyper(cfg), step,
+                                        1.0, float(c_ref), nthreads=8)
+        step += 1
+        for i in range(len(shapes)):
+            got = dict(p=host_f32(ls.p[i]), m=host_f32(ls.m[i]), v=host_f32(ls.v[i]), lp=synth.bits16(ls.p_lp[i]))
+            assert_state_close(got, refs[i], "iteration %d, tensor %d (%s)" % (it, i, shapes[i][0]))
