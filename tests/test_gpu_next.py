@@ -413,6 +413,75 @@ def test_auto_iteration_replays_as_a_graph():
     assert state_ref.skipped == 2
 
 
+def test_list_iteration_replays_as_a_graph():
+    """The same for a tensor list large enough (about 1000 work items) that the update kernel draws
+    its late items on demand: the counters in the plan's table are used and cleared inside every
+    replay, so ONE captured graph still serves every iteration, skipped ones included."""
+    shapes = synth.scaled_shapes(synth.llama3_8b_shapes(), 2048, ragged=True)
+    cfg = synth.FlatConfig("t", 0, seed=93, gdt="bf16", loss_scale=1.0, m_std=1e-4, v_std=1e-8, max_norm=0.1)
+    ls = synth.make_list(shapes, cfg, device="cuda")
+    plan = ma.MultiPlan(ls.p, ls.m, ls.v, ls.g, ls.p_lp)
+    assert plan.plan.step_chunks >= 512
+    h_ref, h = oracle_hyper(cfg), _hyper(cfg)
+    scaler, scfg = ma.new_scaler(1.0, 3), ma.scaler_config(window=1000)
+    ws, res = ma.workspace(), ma.new_result()
+    refs = [dict(p=host_f32(ls.p[i]), m=host_f32(ls.m[i]), v=host_f32(ls.v[i]), lp=synth.bits16(ls.p_lp[i]),
+                 pdt="bf16") for i in range(len(shapes))]
+
+    def iteration():
+        ma.multi_overflow_norm_auto(plan, scaler, res, ws)
+        ma.multi_adamw_step_auto(plan, h, scaler, res, cfg.max_norm)
+        ma.scaler_update(scaler, res, scfg)
+
+    def feed(it, bad):
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(900 + it)
+        synth._fill_grad(ls.flat.g, 1e-3, 1.0, gen)
+        if bad:
+            ls.g[it % len(shapes)].view(torch.int16)[0] = 0x7F81
+        return [host_grad(g) for g in ls.g]
+
+    applied = 3
+    scale = 1.0
+
+    def check(it, g_hosts, bad):
+        nonlocal applied, scale
+        torch.cuda.synchronize()
+        ov, ss = ma.read_result(res)
+        assert ov == bad, it
+        assert plan.table[:64].view(torch.int32).cpu().tolist() == [0] * 16, it
+        if bad:
+            scale = max(scale * 0.5, 1.0)
+        else:
+            ss_ref = sum(oracle.overflow_norm(g, "bf16", scale)[1] for g in g_hosts)
+            assert abs(ss - ss_ref) <= 1e-12 * ss_ref
+            c_ref = oracle.clip_coef(ss_ref, float(np.float32(cfg.max_norm)))
+            applied += 1
+            for r, g in zip(refs, g_hosts):
+                r["lp"] = oracle.adamw_step(r["p"], r["m"], r["v"], g, "bf16", "bf16", h_ref, applied, scale,
+                                            float(c_ref), nthreads=8)
+        assert ma.read_scaler(scaler)[2] == applied, it
+        for i in range(len(shapes)):
+            got = dict(p=host_f32(ls.p[i]), m=host_f32(ls.m[i]), v=host_f32(ls.v[i]), lp=synth.bits16(ls.p_lp[i]))
+            assert_state_close(got, refs[i], "graph iteration %d, tensor %d" % (it, i))
+
+    gh = feed(0, False)
+    iteration()
+    check(0, gh, False)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        iteration()
+    torch.cuda.synchronize()
+    for it in range(1, 6):
+        bad = it == 3
+        gh = feed(it, bad)
+        graph.replay()
+        check(it, gh, bad)
+        _ = (ls.flat.p[:1000] * 2).sum().item()      # eager work of the program between replays
+
+
 def test_multi_list_with_bf16_states():
     """A ragged miniature of the 8B-shaped list with p, m, v held in bf16: one scan launch, one gated
     update launch over the prepared list, against the oracle tensor by tensor; then an overflow."""
