@@ -370,8 +370,10 @@ struct FixedItems {
   }
 };
 
-// Items drawn from the pools, MA_STEP_DRAW consecutive ones per draw: a draw costs the block a
-// barrier, which lines up its four otherwise free-running waves.
+// Items drawn from the pools, several consecutive ones per draw: a draw costs the block a barrier,
+// which lines up its four otherwise free-running waves.  Up to MA_STEP_DRAW items per draw, fewer
+// when the pools are small, so that a pool always makes at least four draws per block of its XCD
+// (the last draws decide how evenly the launch ends).
 struct PoolItems {
   StepQueue* q;
   uint32_t* slot;  // two words of LDS
@@ -379,9 +381,15 @@ struct PoolItems {
   uint64_t cur = 0;  // next item of the current draw
   uint32_t left = 0;  // items of the current draw not yet handed out
   uint32_t x, visited = 0, parity = 0;
+  uint32_t draw;
 
   __device__ __forceinline__ PoolItems(uint64_t chunks_, StepQueue* q_, uint32_t* slot_)
-      : q(q_), slot(slot_), chunks(chunks_), x(blockIdx.x & 7) {}
+      : q(q_), slot(slot_), chunks(chunks_), x(blockIdx.x & 7) {
+    uint64_t base, pool;
+    step_pool_of(chunks, x, base, pool);
+    const uint64_t fine = pool / (uint64_t(gridDim.x >> 3) * 4);
+    draw = fine < 1 ? 1u : fine > MA_STEP_DRAW ? uint32_t(MA_STEP_DRAW) : uint32_t(fine);
+  }
 
   __device__ __forceinline__ bool next(uint64_t& out) {
     while (left == 0) {
@@ -389,13 +397,13 @@ struct PoolItems {
       const uint32_t y = (x + visited) & 7;
       uint64_t base, pool;
       step_pool_of(chunks, y, base, pool);
-      if (threadIdx.x == 0) slot[parity] = atomicAdd(&q->next[y], uint32_t(MA_STEP_DRAW));
+      if (threadIdx.x == 0) slot[parity] = atomicAdd(&q->next[y], draw);
       __syncthreads();
       const uint32_t idx = __builtin_amdgcn_readfirstlane(slot[parity]);
       parity ^= 1u;  // the next draw writes the other word: one barrier per draw is enough
       if (idx < pool) {
         const uint64_t rest = pool - idx;
-        left = rest < MA_STEP_DRAW ? uint32_t(rest) : uint32_t(MA_STEP_DRAW);
+        left = rest < draw ? uint32_t(rest) : draw;
         cur = base + idx;
       } else {
         ++visited;
@@ -576,8 +584,15 @@ static int resident_blocks_per_cu(K kernel) {
   return nb;
 }
 
-// Fewest work items of a launch for which every XCD's pool holds at least one.
-constexpr uint64_t kMinItemsForPools = uint64_t(8) << MA_STEP_POOL_SHIFT;
+// Fewest work items of a launch that uses pools.  Measured on 8B-shaped lists scaled down: with
+// 30,000 items (1.3e8 elements) pools cost 1.5-2 % (the second loop's start-up and the eight empty
+// draws at the end weigh more than the evening-out gains), with 120,000 items they gain 0.5 %, from
+// 500,000 items on 0.6-0.8 %.
+#ifndef MA_STEP_POOL_MIN_ITEMS
+#define MA_STEP_POOL_MIN_ITEMS 65536
+#endif
+constexpr uint64_t kMinItemsForPools = MA_STEP_POOL_MIN_ITEMS;
+static_assert(kMinItemsForPools >= (uint64_t(8) << MA_STEP_POOL_SHIFT), "every XCD's pool must hold an item");
 
 template <int SDT, int GDT, int PDT>
 static hipError_t launch_step_typed(const Desc* row_host, const Desc* table_dev, uint32_t rows,

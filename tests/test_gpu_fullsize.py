@@ -387,3 +387,77 @@ def test_flat_fp32_states_beyond_2_to_32():
     fl.g.view(torch.int16)[(1 << 32) + 1] = 0x7E00
     ma.overflow_norm(fl.g, 4096.0, res, ws, index=1)
     assert ma.read_result(res, 1)[0] is True
+
+
+def test_list_with_late_items_drawn_on_demand_eager_and_graph():
+    """A 1/16-scale 8B-shaped list (5.0e8 elements, 122,592 work items): large enough that the update
+    kernel hands the last part of every XCD's share out on demand.  One eager iteration, then ONE
+    captured graph (scan, gated update, loss-scale update, all reading their inputs on the device)
+    replayed three times, the second replay skipped by a NaN.  After every iteration EVERY element
+    of every tensor is compared with the oracle: each work item is processed exactly once whichever
+    block draws it; and the counters at the head of the plan's table read zero again (a stale
+    counter would leave late items of the next launch undone)."""
+    _need_gib(20)
+    shapes = synth.scaled_shapes(synth.llama3_8b_shapes(), 16, ragged=True)
+    cfg = synth.FlatConfig("t", 0, seed=95, m_std=1e-4, v_std=1e-8, max_norm=1.0)
+    ls = synth.make_list(shapes, cfg, device="cuda", align_elems=1)
+    plan = ma.MultiPlan(ls.p, ls.m, ls.v, ls.g, ls.p_lp)
+    assert plan.plan.step_chunks >= 65536
+    h_ref, h = oracle_hyper(cfg), _hyper(cfg)
+    scaler, scfg = ma.new_scaler(1.0, 41), ma.scaler_config(window=1000)
+    ws, res = ma.workspace(), ma.new_result()
+    refs = [dict(p=host_f32(ls.p[i]), m=host_f32(ls.m[i]), v=host_f32(ls.v[i]), lp=synth.bits16(ls.p_lp[i]),
+                 pdt="bf16") for i in range(len(shapes))]
+    head = lambda: plan.table[:64].view(torch.int32).cpu().tolist()
+    assert head() == [0] * 16
+
+    def iteration():
+        ma.multi_overflow_norm_auto(plan, scaler, res, ws)
+        ma.multi_adamw_step_auto(plan, h, scaler, res, cfg.max_norm)
+        ma.scaler_update(scaler, res, scfg)
+
+    def feed(it, bad):
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(950 + it)
+        synth._fill_grad(ls.flat.g, 1e-3, 1.0, gen)
+        if bad:
+            ls.g[-1].view(torch.int16)[-1] = 0x7FC0       # the very last element of the list
+        return [host_grad(g) for g in ls.g]
+
+    applied = 41
+
+    def check(it, g_hosts, bad):
+        nonlocal applied
+        torch.cuda.synchronize()
+        ov, ss = ma.read_result(res)
+        assert ov == bad, it
+        assert head() == [0] * 16, it
+        if not bad:
+            ss_ref = sum(oracle.overflow_norm(g, "bf16", 1.0, nthreads=THREADS)[1] for g in g_hosts)
+            assert abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref
+            c_ref = oracle.clip_coef(ss_ref, 1.0)
+            assert np.float32(ma.clip_coef(ss, 1.0)) == c_ref
+            applied += 1
+            for r, g in zip(refs, g_hosts):
+                r["lp"] = oracle.adamw_step(r["p"], r["m"], r["v"], g, "bf16", "bf16", h_ref, applied, 1.0,
+                                            float(c_ref), nthreads=THREADS)
+        assert ma.read_scaler(scaler)[2] == applied, it
+        for i in range(len(shapes)):
+            got = dict(p=host_f32(ls.p[i]), m=host_f32(ls.m[i]), v=host_f32(ls.v[i]), lp=synth.bits16(ls.p_lp[i]))
+            assert_state_close(got, refs[i], "iteration %d, tensor %d (%s)" % (it, i, shapes[i][0]))
+
+    gh = feed(0, False)
+    iteration()
+    check(0, gh, False)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        iteration()
+    torch.cuda.synchronize()
+    for it in range(1, 4):
+        bad = it == 2
+        gh = feed(it, bad)
+        graph.replay()
+        check(it, gh, bad)
+        _ = (ls.flat.p[:1000] * 2).sum().item()      # eager work of the program between replays

@@ -414,9 +414,9 @@ def test_auto_iteration_replays_as_a_graph():
 
 
 def test_list_iteration_replays_as_a_graph():
-    """The same for a tensor list large enough (about 1000 work items) that the update kernel draws
-    its late items on demand: the counters in the plan's table are used and cleared inside every
-    replay, so ONE captured graph still serves every iteration, skipped ones included."""
+    """The same for a tensor list (about 1000 work items): ONE captured graph serves every iteration,
+    skipped ones included, and the counters at the head of the plan's table read zero after every
+    replay."""
     shapes = synth.scaled_shapes(synth.llama3_8b_shapes(), 2048, ragged=True)
     cfg = synth.FlatConfig("t", 0, seed=93, gdt="bf16", loss_scale=1.0, m_std=1e-4, v_std=1e-8, max_norm=0.1)
     ls = synth.make_list(shapes, cfg, device="cuda")

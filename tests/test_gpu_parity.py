@@ -432,12 +432,11 @@ def test_two_sub_groups_on_two_streams():
         assert_state_close(_host_state(st, "bf16"), refs[k], "stream %d" % k)
 
 
-def test_multi_list_repeated_launches_share_out_late_items():
-    """A 1/512-scale 8B-shaped list (about 4000 work items): large enough that the update kernel
-    hands the last part of every XCD's share out on demand.  Four iterations on one plan, the third
-    one skipped by an overflow: every element is updated exactly once per applied iteration,
-    whichever block took its work item, and the plan's counters are back at zero after every launch
-    (a stale counter would leave late items of the next launch undone)."""
+def test_multi_list_repeated_launches():
+    """A 1/512-scale 8B-shaped list (about 4000 work items), four iterations on one plan, the third
+    one skipped by an overflow: every element is updated exactly once per applied iteration and the
+    counters at the head of the plan's table read zero after every launch.  (Lists of this size keep
+    fixed shares; tests/test_gpu_fullsize.py has the same at a size that draws late items on demand.)"""
     shapes = synth.scaled_shapes(synth.llama3_8b_shapes(), 512, ragged=True)
     cfg = synth.FlatConfig("t", 0, seed=77, m_std=1e-4, v_std=1e-8, step=100, max_norm=0.3)
     ls = synth.make_list(shapes, cfg, device="cuda", align_elems=1)
