@@ -42,8 +42,8 @@ SCAN_BYTES_PER_PARAM = 2.0     # scan kernel: read g
 # profiles/hbm_traffic_counters__llama3_8b.txt).  Valid only for the kernel sources they were taken
 # with: when the digest of the kernel sources differs, the figure is reported as null.
 MEASURED_TRAFFIC = {
-    "kernel_sha256": "54f2ffb8ac88e39b11d6b56a8f313ea858e5bc9dc52b1ea6b6932be42777ff76",
-    "llama3_8b": 224846917852,
+    "kernel_sha256": "7744dde52cc03600bc1525d7a939b1b342d21e77beab6dbeed253946a3bbb833",
+    "llama3_8b": 224846638326,
 }
 
 

@@ -67,16 +67,14 @@ __global__ __launch_bounds__(kBlock) void norm_flat_kernel(Desc row, uint64_t ch
   norm_block_finish<GDT>(acc, partials);
 }
 
-// Largest row index in [lo, rows) whose first work item is <= c.  All operands are uniform
+// Largest row index in [lo, rows) whose first scan work item is <= c.  All operands are uniform
 // across the block, so this runs on the scalar unit.
-template <bool STEP>
 __device__ __forceinline__ uint32_t find_row(const Desc* table, uint32_t lo, uint32_t rows,
                                              uint64_t c) {
   uint32_t hi = rows;
   while (hi - lo > 1) {
     const uint32_t mid = lo + (hi - lo) / 2;
-    const uint64_t first = STEP ? table[mid].step_chunk0 : table[mid].norm_chunk0;
-    if (first <= c) {
+    if (table[mid].norm_chunk0 <= c) {
       lo = mid;
     } else {
       hi = mid;
@@ -94,7 +92,7 @@ __global__ __launch_bounds__(kBlock) void norm_multi_kernel(const Desc* __restri
   uint32_t r = 0;
   for (WorkIter<MA_NORM_MAP> w(chunks); w.c < w.end; w.c += w.stride) {
     const uint64_t c = w.c;
-    r = find_row<false>(table, r, rows, c);
+    r = find_row(table, r, rows, c);
     const Desc* d = table + r;
     norm_chunk<GDT>(acc, d->g, d->n, d->norm_head, c - d->norm_chunk0);
   }
