@@ -72,7 +72,7 @@ def log(*a):
 class Workload:
     """Holds device state and enqueues one step; records (scan, update) event pairs."""
 
-    def __init__(self, name, ma, layout="streams", placement="region"):
+    def __init__(self, name, ma, layout="streams", placement="region", rotate=1):
         self.name, self.ma, self.layout, self.placement = name, ma, "flat", placement
         # placement "region": the state is cut from one whole-device allocation at the offset
         # that splits its traffic evenly over two of the three 96 GiB HBM regions (hbm.py);
@@ -188,11 +188,19 @@ class Workload:
             self.cfg = cfg
             self.flat = synth.make_flat(cfg, device="cuda",
                                         arena=place(synth.flat_state_bytes(cfg.n), synth.flat_traffic(cfg.n)))
+            # --rotate K: K distinct sub-groups of this shape, one per step in turn, so that a small
+            # sub-group is measured from HBM and not from the caches (256 MB of Infinity Cache)
+            self.flats = [self.flat]
+            for k in range(1, rotate):
+                other = synth.FlatConfig(**{**cfg.__dict__, "seed": cfg.seed + 1000 * k})
+                self.flats.append(synth.make_flat(other, device="cuda"))
             self.n = cfg.n
             self.t = cfg.step
             self.kind = "flat"
-            self.desc = "flat sub-group n=%d, %s grads, loss_scale %g, max_norm %g" % (
-                cfg.n, cfg.gdt, cfg.loss_scale, cfg.max_norm)
+            self.desc = "flat sub-group n=%d, %s grads, loss_scale %g, max_norm %g%s" % (
+                cfg.n, cfg.gdt, cfg.loss_scale, cfg.max_norm,
+                "" if rotate == 1 else "; %d distinct sub-groups in rotation (%.0f MB of state)" % (
+                    rotate, rotate * synth.flat_state_bytes(cfg.n) / 1e6))
         c = self.cfg
         self.h = ma.hyper(c.lr, c.beta1, c.beta2, c.eps, c.weight_decay, 1)
 
@@ -227,7 +235,7 @@ class Workload:
             # the last micro-batch of an iteration is accumulated and scanned in one pass
             ma.grad_accumulate_scan(self.acc, self.bg, False, c.loss_scale, self.res, self.ws)
         elif self.kind == "flat":
-            f = self.flat
+            f = self.flats[self.t % len(self.flats)]
             ma.overflow_norm(f.g, c.loss_scale, self.res, self.ws)
             if record:
                 ev[1].record()
@@ -305,6 +313,9 @@ def main():
     ap.add_argument("--placement", default="region", choices=["region", "plain"],
                     help="'region' (default): cut the state from one whole-device allocation so that its "
                          "traffic splits evenly over two 96 GiB HBM regions; 'plain': a fresh allocation")
+    ap.add_argument("--rotate", type=int, default=1, metavar="K",
+                    help="flat_1e8 / fp16_5e7 / c1 only: step K distinct sub-groups of the workload's shape in "
+                         "turn, so that a small sub-group is read from HBM rather than from the caches")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample", type=int, default=1 << 28)
     ap.add_argument("--cpu-passes", type=int, default=4)
@@ -322,7 +333,7 @@ def main():
 
     torch.cuda.set_device(0)
     t_setup = time.perf_counter()
-    wl = Workload(args.workload, ma, args.layout, args.placement)
+    wl = Workload(args.workload, ma, args.layout, args.placement, max(1, args.rotate))
     torch.cuda.synchronize()
     log("setup %.1f s: %s" % (time.perf_counter() - t_setup, wl.desc))
 
@@ -390,6 +401,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": args.workload, "description": wl.desc, "elements": wl.n,
                    "layout": wl.layout, "placement": wl.placement,
+                   "rotating_sets": len(getattr(wl, "flats", [None])),
                    "grad_dtype": wl.cfg.gdt, "param_copy_dtype": wl.cfg.pdt,
                    "max_norm": wl.cfg.max_norm, "loss_scale": wl.cfg.loss_scale,
                    "sumsq_last_step": ss},
