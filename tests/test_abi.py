@@ -330,3 +330,40 @@ def test_header_is_plain_c_and_layouts_match_the_binding(tmp_path):
         for field, _ in cls._fields_:
             assert got[(cname, field)] == getattr(cls, field).offset, (cname, field)
     assert got[("ma_norm_result", "size")] == 16 and got[("ma_scaler_state", "size")] == 24
+
+
+def test_a_plain_c_program_links_and_calls_the_host_side(tmp_path):
+    """A C99 translation unit that includes only include/ma.h links against the library and calls
+    its host-side entry points (nothing here needs a GPU)."""
+    import subprocess
+    src = tmp_path / "host_calls.c"
+    src.write_text(r'''
+#include "ma.h"
+#include <stdio.h>
+int main(void) {
+  ma_model_dims d = {152064u, 3584u, 18944u, 512u, 3584u};   /* Qwen2.5-7B shapes */
+  ma_pool_layout lay;
+  int rc = ma_pool_layout_compute(&d, 1u, 2u, 1u, 1u, &lay);
+  ma_hyper h = {1e-5f, 0.9f, 0.999f, 1e-8f, 0.01f, 1};
+  float sc[9];
+  int rc2 = ma_step_scalars(&h, 100, 1.0f, 1.0f, sc);
+  int rc3 = ma_step_scalars(&h, 0, 1.0f, 1.0f, sc);           /* step < 1: an argument error */
+  printf("%d %d %d %llu %llu %.9g %.9g %d\n", ma_version() >= 100, rc, rc2,
+         (unsigned long long)lay.total_bytes, (unsigned long long)lay.uniform_bytes,
+         (double)ma_clip_coef(100.0, 1.0f), (double)sc[0], rc3);
+  printf("%s\n", ma_last_error());
+  return 0;
+}
+''')
+    exe = tmp_path / "host_calls"
+    libdir = os.path.dirname(ma.LIB_PATH)
+    subprocess.run(["gcc", "-std=c99", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"), str(src),
+                    "-L", libdir, "-l:" + os.path.basename(ma.LIB_PATH), "-Wl,-rpath," + libdir, "-o", str(exe)],
+                   check=True, capture_output=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split("\n")
+    f = out[0].split()
+    assert f[:3] == ["1", "0", "0"]
+    lay = ma.pool_layout(152064, 3584, 18944, 512, 3584, 1, 2)
+    assert int(f[3]) == lay.total_bytes and int(f[4]) == lay.uniform_bytes
+    assert abs(float(f[5]) - 0.1) < 1e-7 and np.float32(float(f[6])) == np.float32(0.9)
+    assert int(f[7]) == ma.MA_ERR_ARG and "step" in out[1]
