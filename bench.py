@@ -37,17 +37,22 @@ STEP_BYTES_PER_PARAM = 28.0    # update kernel: read p,m,v (12) + g (2), write p
 SCAN_BYTES_PER_PARAM = 2.0     # scan kernel: read g
 
 
-# HBM bytes per launch of the update kernel from hardware counters (rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE, scaled by a plain copy of known size; summary in
-# profiles/hbm_traffic_counters__llama3_8b.txt).  Valid only for the kernel sources they were taken
-# with: when the digest of the kernel sources differs, the figure is reported as null.
+# HBM bytes per launch of each workload's dominant kernel from hardware counters (rocprofv3 --pmc
+# FETCH_SIZE / WRITE_SIZE, scaled by a plain copy of known size; summaries under profiles/).  Valid
+# only for the kernel sources they were taken with: when the digest of the kernel sources differs,
+# the figure is reported as null.
 MEASURED_TRAFFIC = {
-    "kernel_sha256": "7744dde52cc03600bc1525d7a939b1b342d21e77beab6dbeed253946a3bbb833",
+    "kernel_sha256": "0692da2c999e1fc0bc7c8ae8d0363e2e496618dc6eb34af55b06165e99bf8be4",
     "llama3_8b": 224846638326,
+    "fp32grad_8b": 240908401047,
+    "auto_fp16_8b": 224846863953,
+    "qwen14b_4sub": 87973205605,
+    "bf16_states_8b": 112423225904,
+    "accumulate_8b": 80301744474,
 }
 
 
-KERNEL_SOURCES = ("ma_device.h", "ma_internal.h", "ma_norm.hip", "ma_adamw.hip")
+KERNEL_SOURCES = ("ma_device.h", "ma_internal.h", "ma_norm.hip", "ma_adamw.hip", "ma_accum.hip")
 
 
 def kernel_digest():
