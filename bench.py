@@ -42,13 +42,13 @@ SCAN_BYTES_PER_PARAM = 2.0     # scan kernel: read g
 # only for the kernel sources they were taken with: when the digest of the kernel sources differs,
 # the figure is reported as null.
 MEASURED_TRAFFIC = {
-    "kernel_sha256": "0692da2c999e1fc0bc7c8ae8d0363e2e496618dc6eb34af55b06165e99bf8be4",
-    "llama3_8b": 224846638326,
-    "fp32grad_8b": 240908401047,
-    "auto_fp16_8b": 224846863953,
-    "qwen14b_4sub": 87973205605,
-    "bf16_states_8b": 112423225904,
-    "accumulate_8b": 80301744474,
+    "kernel_sha256": "5ca51ac993e463c96a1323d8d8754851c2ef9cc1242556443dde84f2ca0523c3",
+    "llama3_8b": 224846990735,
+    "fp32grad_8b": 240908548336,
+    "auto_fp16_8b": 224846981559,
+    "qwen14b_4sub": 87973119559,
+    "bf16_states_8b": 112423220365,
+    "accumulate_8b": 80301741587,
 }
 
 

@@ -49,7 +49,7 @@ constexpr int kNoLp = 3;  // update kernel variant that writes no low-precision 
 #define MA_STEP_PACE_BF16 0  // the same for states held in bf16 (either kernel)
 #endif
 #ifndef MA_STEP_POOL_SHIFT
-#define MA_STEP_POOL_SHIFT 6  // tensor lists: the last 1/2^k of every XCD's share is handed out on demand
+#define MA_STEP_POOL_SHIFT 5  // tensor lists: the last 1/2^k of every XCD's share is handed out on demand
 #endif
 #ifndef MA_STEP_DRAW
 #define MA_STEP_DRAW 8  // work items a block takes from a pool at a time
