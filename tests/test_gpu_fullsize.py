@@ -461,3 +461,45 @@ def test_list_with_late_items_drawn_on_demand_eager_and_graph():
         graph.replay()
         check(it, gh, bad)
         _ = (ls.flat.p[:1000] * 2).sum().item()      # eager work of the program between replays
+
+
+def test_bf16_state_list_with_late_items_drawn_on_demand():
+    """The same size class for a list whose p, m, v are held in bf16 (1/8-scale 8B shapes, 1.0e9
+    elements, work items of 12,288 elements): two iterations on one plan, every truncated pattern of
+    every tensor against the oracle, counters back at zero."""
+    _need_gib(24)
+    shapes = synth.scaled_shapes(synth.llama3_8b_shapes(), 8, ragged=True)
+    cfg = synth.FlatConfig("t", 0, seed=97, m_std=1e-3, v_std=1e-6, lr=1e-2, weight_decay=0.1, eps=1e-6,
+                           max_norm=1.0)
+    ls = synth.make_list(shapes, cfg, device="cuda", align_elems=1)
+    shift = lambda t: (t.view(torch.int32) >> 16).to(torch.int16).view(torch.bfloat16).contiguous()
+    fp, fm, fv = shift(ls.flat.p), shift(ls.flat.m), shift(ls.flat.v)
+    offs = [t.data_ptr() // 4 - ls.flat.p.data_ptr() // 4 for t in ls.p]
+    cut = lambda buf: [buf[o:o + n] for o, (_, n) in zip(offs, shapes)]
+    P, M, V = cut(fp), cut(fm), cut(fv)
+    grads = list(ls.g)
+    del ls.p, ls.m, ls.v, ls.p_lp
+    ls.flat.p = ls.flat.m = ls.flat.v = ls.flat.p_lp = None      # the fp32 originals are no longer needed
+    torch.cuda.empty_cache()
+    plan = ma.MultiPlanBF16(P, M, V, grads)
+    assert plan.plan.step_chunks >= 65536 and plan.plan.sdt == ma.MA_BF16
+    refs = [(synth.bits16(P[i]), synth.bits16(M[i]), synth.bits16(V[i])) for i in range(len(shapes))]
+    g_hosts = [host_grad(g) for g in grads]
+    ss_ref = sum(oracle.overflow_norm(g, "bf16", 1.0, nthreads=THREADS)[1] for g in g_hosts)
+    c_ref = oracle.clip_coef(ss_ref, 1.0)
+    assert c_ref < 1
+    ws, res = ma.workspace(), ma.new_result()
+    for step in (5, 6):
+        ma.multi_overflow_norm(plan, 1.0, res, ws)
+        ma.multi_adamw_step_gated(plan, _hyper(cfg), step, 1.0, res, cfg.max_norm)
+        ov, ss = ma.read_result(res)
+        assert not ov and abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref
+        assert plan.table[:64].view(torch.int32).cpu().tolist() == [0] * 16
+        for i in range(len(shapes)):
+            rp, rm, rv = refs[i]
+            oracle.adamw_step_bf16(rp, rm, rv, g_hosts[i], "bf16", oracle_hyper(cfg), step, 1.0, float(c_ref),
+                                   nthreads=THREADS)
+            for name, t, r in (("p", P[i], rp), ("m", M[i], rm), ("v", V[i], rv)):
+                got = synth.bits16(t)
+                assert np.array_equal(got, r), "step %d tensor %d (%s) %s: %d patterns differ" % (
+                    step, i, shapes[i][0], name, int((got != r).sum()))
