@@ -244,6 +244,22 @@ def test_14b_class_four_sub_groups_sampled():
     assert not ov and abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref
     assert np.float32(ma.clip_coef(ss, 1.0)) == c_ref
     assert_state_close(_sample_state(fl, ranges, "bf16"), before, "14B sub-groups sample")
+    # a second iteration with every sub-group prepared as a one-tensor list (the form in which a flat
+    # sub-group gets its late work items drawn on demand)
+    plans = []
+    for k in range(4):
+        s = slice(k * sub, (k + 1) * sub)
+        plans.append(ma.MultiPlan([fl.p[s]], [fl.m[s]], [fl.v[s]], [fl.g[s]], [fl.p_lp[s]]))
+    before["lp"] = oracle.adamw_step(before["p"], before["m"], before["v"], g_s, "bf16", "bf16",
+                                     oracle_hyper(cfg), 101, 1.0, float(c_ref), nthreads=THREADS)
+    for k in range(4):
+        ma.multi_overflow_norm(plans[k], 1.0, parts, ws, index=k)
+    ma.norm_combine(parts, 4, res)
+    for k in range(4):
+        ma.multi_adamw_step_gated(plans[k], _hyper(cfg), 101, 1.0, res, 1.0)
+    ov, ss2 = ma.read_result(res)
+    assert not ov and ss2 == ss
+    assert_state_close(_sample_state(fl, ranges, "bf16"), before, "14B sub-groups as one-tensor lists")
 
 
 def test_flat_sub_group_beyond_2_to_31():
