@@ -8,7 +8,7 @@ Measured on MI355X (two-stream write and mixed read/write probes over a whole-de
 * one allocation that takes (nearly) all free device memory maps linearly onto the regions: byte
   offset x of the allocation lies in region x // 96 GiB;
 * the update kernel is fastest when its traffic splits evenly over two regions (measured on the
-  8B-shaped state: 6.37 TB/s with the state straddling a region boundary half and half, 5.85-6.0
+  8B-shaped state: 6.4 TB/s with the state straddling a region boundary half and half, 5.85-6.0
   TB/s with 80 % of it inside one region; three-way splits were not better than the even two-way
   split).
 
