@@ -471,3 +471,53 @@ def test_multi_list_repeated_launches():
         for i in range(len(shapes)):
             got = dict(p=host_f32(ls.p[i]), m=host_f32(ls.m[i]), v=host_f32(ls.v[i]), lp=synth.bits16(ls.p_lp[i]))
             assert_state_close(got, refs[i], "iteration %d, tensor %d (%s)" % (it, i, shapes[i][0]))
+
+
+def test_randomised_sizes_alignments_and_hyper_parameters():
+    """150 seeded random cases of the flat scan + gated update: sizes from 0 to 4e5, every buffer at
+    its own element offset from an aligned base (0..8), all gradient and copy dtypes, hyper-parameters
+    over several decades, loss scales 1..65536, with and without clipping.  p, m, v must equal the
+    oracle's bit for bit (and the copy with them); the sum of squares to 1e-11 (fp64 on both sides,
+    different summation order)."""
+    rng = np.random.default_rng(20250527)
+    ws = ma.workspace()
+    for case in range(150):
+        n = int(rng.choice([rng.integers(0, 64), rng.integers(64, 5000), rng.integers(5000, 40000),
+                            rng.integers(40000, 400000)]))
+        gdt = str(rng.choice(["bf16", "f16", "f32"]))
+        pdt = str(rng.choice(["bf16", "f16"]))
+        offs = [int(rng.integers(0, 9)) for _ in range(5)]
+        if rng.random() < 0.5:
+            offs = [offs[0]] * 5
+        S = float(2.0 ** rng.integers(0, 17)) if gdt != "f32" else 1.0
+        cfg = synth.FlatConfig("z", n, seed=int(rng.integers(1 << 30)), gdt="bf16" if gdt == "f32" else gdt, pdt=pdt,
+                               loss_scale=S, m_std=float(10 ** rng.uniform(-6, -2)),
+                               v_std=float(10 ** rng.uniform(-10, -4)), g_std=float(10 ** rng.uniform(-6, -1)),
+                               step=int(rng.choice([1, 2, 7, 100, 100000])), lr=float(10 ** rng.uniform(-6, -1)),
+                               beta1=float(rng.choice([0.0, 0.5, 0.9, 0.99])),
+                               beta2=float(rng.choice([0.0, 0.9, 0.999, 0.9999])), eps=float(10 ** rng.uniform(-10, -3)),
+                               weight_decay=float(rng.choice([0.0, 0.01, 0.3])),
+                               max_norm=float(rng.choice([0.0, 0.01, 1.0, 100.0])))
+        st = synth.make_flat(cfg, device="cuda", n=n)
+
+        def view(t, o):
+            base = torch.zeros(n + 16, dtype=t.dtype, device="cuda")
+            base[o:o + n].copy_(t)
+            return base[o:o + n]
+
+        g = st.g if gdt != "f32" else st.g.to(torch.float32) * 1.7
+        p, m, v, g, lp = (view(t, o) for t, o in zip((st.p, st.m, st.v, g, st.p_lp), offs))
+        ref = dict(p=host_f32(p), m=host_f32(m), v=host_f32(v), lp=synth.bits16(lp), pdt=pdt)
+        ov_ref, ss_ref, _ = oracle.optimizer_step(ref["p"], ref["m"], ref["v"], host_grad(g), gdt, ref["lp"], pdt,
+                                                  oracle_hyper(cfg), cfg.step, S, cfg.max_norm)
+        res = ma.new_result()
+        ma.overflow_norm(g, S, res, ws)
+        ma.adamw_step_gated(p, m, v, g, lp, _hyper(cfg), cfg.step, S, res, cfg.max_norm)
+        ov, ss = ma.read_result(res)
+        what = "case %d: n=%d gdt=%s pdt=%s offsets=%s %r" % (case, n, gdt, pdt, offs, cfg)
+        assert ov == ov_ref is False, what
+        assert abs(ss - ss_ref) <= 1e-11 * ss_ref, what
+        got = dict(p=host_f32(p), m=host_f32(m), v=host_f32(v), lp=synth.bits16(lp))
+        for k in ("p", "m", "v"):
+            assert np.array_equal(got[k].view(np.uint32), ref[k].view(np.uint32)), (k, what)
+        assert np.array_equal(got["lp"], ref["lp"]), what
