@@ -521,3 +521,62 @@ def test_randomised_sizes_alignments_and_hyper_parameters():
         for k in ("p", "m", "v"):
             assert np.array_equal(got[k].view(np.uint32), ref[k].view(np.uint32)), (k, what)
         assert np.array_equal(got["lp"], ref["lp"]), what
+
+
+def test_randomised_tensor_lists():
+    """40 seeded random tensor lists: 1 to 40 tensors of 0 to 60,000 elements, each of the five buffers
+    of each tensor at its own element offset (so rows with every combination of packet-path and
+    scalar-path alignment meet in one launch), both gradient dtypes, with the parameter copy or
+    without; p, m, v and the copy bit for bit against the oracle run tensor by tensor."""
+    rng = np.random.default_rng(4242)
+    ws = ma.workspace()
+    tensors = elements = 0
+    for case in range(40):
+        count = int(rng.integers(1, 41))
+        gdt = str(rng.choice(["bf16", "f16", "f32"]))
+        pdt = str(rng.choice(["bf16", "f16"]))
+        with_lp = bool(rng.random() < 0.8)
+        S = float(2.0 ** rng.integers(0, 12)) if gdt != "f32" else 1.0
+        cfg = synth.FlatConfig("z", 0, seed=int(rng.integers(1 << 30)), gdt="bf16" if gdt == "f32" else gdt, pdt=pdt,
+                               loss_scale=S, m_std=1e-4, v_std=1e-8, step=int(rng.integers(1, 50)),
+                               lr=float(10 ** rng.uniform(-5, -2)), max_norm=float(rng.choice([0.0, 0.05, 10.0])))
+        P, M, V, G, L = [], [], [], [], []
+        for k in range(count):
+            n = int(rng.choice([0, rng.integers(1, 9), rng.integers(9, 5000), rng.integers(5000, 60000)]))
+            st = synth.make_flat(synth.FlatConfig(**{**cfg.__dict__, "seed": cfg.seed + k, "n": n}), device="cuda", n=n)
+            same = rng.random() < 0.5
+            o0 = int(rng.integers(0, 9))
+
+            def view(t):
+                o = o0 if same else int(rng.integers(0, 9))
+                base = torch.zeros(n + 16, dtype=t.dtype, device="cuda")
+                base[o:o + n].copy_(t)
+                return base[o:o + n]
+
+            g = st.g if gdt != "f32" else st.g.to(torch.float32) * 0.9
+            for lst, t in ((P, st.p), (M, st.m), (V, st.v), (G, g), (L, st.p_lp)):
+                lst.append(view(t))
+        refs = [dict(p=host_f32(P[k]), m=host_f32(M[k]), v=host_f32(V[k]), lp=synth.bits16(L[k]), pdt=pdt)
+                for k in range(count)]
+        g_hosts = [host_grad(g) for g in G]
+        ss_ref = sum(oracle.overflow_norm(g, gdt, S)[1] for g in g_hosts)
+        c_ref = oracle.clip_coef(ss_ref, float(np.float32(cfg.max_norm)))
+        for r, g in zip(refs, g_hosts):
+            new_lp = oracle.adamw_step(r["p"], r["m"], r["v"], g, gdt, pdt, oracle_hyper(cfg), cfg.step, S, float(c_ref))
+            if with_lp:
+                r["lp"] = new_lp
+        plan = ma.MultiPlan(P, M, V, G, L if with_lp else None)
+        res = ma.new_result()
+        ma.multi_overflow_norm(plan, S, res, ws)
+        ma.multi_adamw_step_gated(plan, _hyper(cfg), cfg.step, S, res, cfg.max_norm)
+        ov, ss = ma.read_result(res)
+        what = "case %d: %d tensors, gdt=%s pdt=%s copy=%s" % (case, count, gdt, pdt, with_lp)
+        assert not ov and abs(ss - ss_ref) <= 1e-11 * max(ss_ref, 1e-300), what
+        assert np.float32(ma.clip_coef(ss, cfg.max_norm)) == c_ref, what
+        for k in range(count):
+            for name, t in (("p", P[k]), ("m", M[k]), ("v", V[k])):
+                assert np.array_equal(host_f32(t).view(np.uint32), refs[k][name].view(np.uint32)), (what, k, name)
+            assert np.array_equal(synth.bits16(L[k]), refs[k]["lp"]), (what, k, "copy")
+        tensors += count
+        elements += plan.total
+    assert tensors > 400 and elements > 3_000_000       # the draw really covers what the docstring says
