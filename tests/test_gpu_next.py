@@ -618,3 +618,64 @@ def test_multi_list_with_fp32_gradients():
         G32[11][0] = float("inf")
         ma.multi_overflow_norm(plan, S, res, ws)
         assert ma.read_result(res)[0] is True
+
+
+def test_randomised_bf16_states_and_accumulation():
+    """Seeded random cases for the two rows beyond the basic step: 80 bf16-state steps (sizes 0..3e5,
+    each buffer at its own element offset, all gradient dtypes, random hyper-parameters, gated) and
+    80 accumulation sequences (1 to 5 micro-batches, the last one fused with the scan); bit patterns
+    against the oracle."""
+    rng = np.random.default_rng(777)
+    ws = ma.workspace()
+
+    def view(t, n, o):
+        base = torch.zeros(n + 16, dtype=t.dtype, device="cuda")
+        base[o:o + n].copy_(t)
+        return base[o:o + n]
+
+    for case in range(80):
+        n = int(rng.choice([rng.integers(0, 40), rng.integers(40, 9000), rng.integers(9000, 300000)]))
+        gdt = str(rng.choice(["bf16", "f16", "f32"]))
+        S = float(2.0 ** rng.integers(0, 14)) if gdt != "f32" else 1.0
+        cfg = synth.FlatConfig("z", n, seed=int(rng.integers(1 << 30)), gdt="bf16" if gdt == "f32" else gdt,
+                               loss_scale=S, m_std=1e-3, v_std=1e-6, step=int(rng.integers(1, 200)),
+                               lr=float(10 ** rng.uniform(-4, -1)), weight_decay=float(rng.choice([0.0, 0.1])),
+                               eps=float(10 ** rng.uniform(-8, -4)), max_norm=float(rng.choice([0.0, 0.05, 5.0])))
+        st, p, m, v = _bf16_state(cfg, n)
+        g = st.g if gdt != "f32" else st.g.to(torch.float32) * 1.3
+        same = rng.random() < 0.5
+        o0 = int(rng.integers(0, 17))
+        p, m, v, g = (view(t, n, o0 if same else int(rng.integers(0, 17))) for t in (p, m, v, g))
+        rp, rm, rv = synth.bits16(p), synth.bits16(m), synth.bits16(v)
+        g_host = host_grad(g)
+        ov_ref, ss_ref = oracle.overflow_norm(g_host, gdt, S)
+        c_ref = oracle.clip_coef(ss_ref, float(np.float32(cfg.max_norm)))
+        oracle.adamw_step_bf16(rp, rm, rv, g_host, gdt, oracle_hyper(cfg), cfg.step, S, float(c_ref))
+        res = ma.new_result()
+        ma.overflow_norm(g, S, res, ws)
+        ma.adamw_step_bf16_gated(p, m, v, g, _hyper(cfg), cfg.step, S, res, cfg.max_norm)
+        what = "bf16-state case %d: n=%d gdt=%s %r" % (case, n, gdt, cfg)
+        assert ma.read_result(res)[0] is False and not ov_ref, what
+        for t, r in ((p, rp), (m, rm), (v, rv)):
+            assert np.array_equal(synth.bits16(t), r), what
+
+    for case in range(80):
+        n = int(rng.choice([rng.integers(0, 40), rng.integers(40, 9000), rng.integers(9000, 300000)]))
+        gdt = str(rng.choice(["bf16", "f16", "f32"]))
+        S = float(2.0 ** rng.integers(0, 14))
+        micro = int(rng.integers(1, 6))
+        acc = view(torch.full((n,), float("nan"), dtype=torch.float32, device="cuda"), n, int(rng.integers(0, 9)))
+        ref = np.full(n, np.nan, np.float32)
+        res = ma.new_result()
+        for k in range(micro):
+            g = view(_micro_grad(n, int(rng.integers(1 << 30)), gdt, S), n, int(rng.integers(0, 9)))
+            oracle.grad_accumulate(ref, host_grad(g), gdt, first=(k == 0))
+            if k < micro - 1:
+                ma.grad_accumulate(acc, g, first=(k == 0))
+            else:
+                ma.grad_accumulate_scan(acc, g, k == 0, S, res, ws)
+        what = "accumulation case %d: n=%d gdt=%s micro=%d" % (case, n, gdt, micro)
+        assert np.array_equal(host_f32(acc).view(np.uint32), ref.view(np.uint32)), what
+        ov_ref, ss_ref = oracle.overflow_norm(ref, "f32", S)
+        ov, ss = ma.read_result(res)
+        assert ov == ov_ref is False and abs(ss - ss_ref) <= 1e-11 * max(ss_ref, 1e-300), what
