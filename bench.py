@@ -39,34 +39,36 @@ SCAN_BYTES_PER_PARAM = 2.0     # scan kernel: read g
 
 # HBM bytes per launch of each workload's dominant kernel from hardware counters (rocprofv3 --pmc
 # FETCH_SIZE / WRITE_SIZE, scaled by a plain copy of known size; summaries under profiles/).  Valid
-# only for the kernel sources they were taken with: when the digest of the kernel sources differs,
-# the figure is reported as null.
-MEASURED_TRAFFIC = {
-    "kernel_sha256": "5ca51ac993e463c96a1323d8d8754851c2ef9cc1242556443dde84f2ca0523c3",
-    "llama3_8b": 224846990735,
-    "fp32grad_8b": 240908548336,
-    "auto_fp16_8b": 224846981559,
-    "qwen14b_4sub": 87973119559,
-    "bf16_states_8b": 112423220365,
-    "accumulate_8b": 80301741587,
+# only for the kernel sources they were taken with: when the digest of the sources a workload's
+# kernels are built from differs, the figure is reported as null.
+STEP_SOURCES = ("ma_device.h", "ma_internal.h", "ma_norm.hip", "ma_adamw.hip")
+ACCUM_SOURCES = ("ma_device.h", "ma_internal.h", "ma_norm.hip", "ma_accum.hip")
+STEP_SHA256 = "e6581c7bde40ca11d98daf2248a3d9872d64f63190af7998662f21e0310abe97"
+ACCUM_SHA256 = "d35323ae850d4db64d1b75c2659fb32abb68dce08c8732172af83adc65c03679"
+MEASURED_TRAFFIC = {      # workload: (bytes per launch, sources, their digest when measured)
+    "llama3_8b": (224846990735, STEP_SOURCES, STEP_SHA256),
+    "fp32grad_8b": (240908548336, STEP_SOURCES, STEP_SHA256),
+    "auto_fp16_8b": (224846981559, STEP_SOURCES, STEP_SHA256),
+    "qwen14b_4sub": (87973119559, STEP_SOURCES, STEP_SHA256),
+    "bf16_states_8b": (112423220365, STEP_SOURCES, STEP_SHA256),
+    "accumulate_8b": (80301752898, ACCUM_SOURCES, ACCUM_SHA256),
 }
 
 
-KERNEL_SOURCES = ("ma_device.h", "ma_internal.h", "ma_norm.hip", "ma_adamw.hip", "ma_accum.hip")
-
-
-def kernel_digest():
+def kernel_digest(sources=STEP_SOURCES):
     import hashlib
     h = hashlib.sha256()
-    for f in KERNEL_SOURCES:
+    for f in sources:
         with open(os.path.join(ROOT, "paper_2505_23254_amd", "csrc", f), "rb") as fh:
             h.update(fh.read())
     return h.hexdigest()
 
 
 def measured_traffic(workload):
-    if workload in MEASURED_TRAFFIC and kernel_digest() == MEASURED_TRAFFIC["kernel_sha256"]:
-        return MEASURED_TRAFFIC[workload]
+    if workload in MEASURED_TRAFFIC:
+        nbytes, sources, digest = MEASURED_TRAFFIC[workload]
+        if kernel_digest(sources) == digest:
+            return nbytes
     return None
 
 

@@ -7,7 +7,8 @@
 // kernel; a persistent grid of one block per CU with the XCD-contiguous work assignment, which
 // keeps the eight XCDs at eight different places of the two buffers (with all blocks sweeping one
 // moving window the kernel was 25 % slower whenever both buffers lay in the same region of HBM).
-// Measured best depth: eight groups per lane in flight for the overwrite, four for the add.
+// Measured best depth: eight groups per lane in flight for the overwrite, four for the add, eight
+// for the add fused with the scan (whose fp64 arithmetic then overlaps more loads).
 //
 // The SCAN variant also runs the overflow check of Sec. IV-D / Algorithm 1 (with its fp32 mask)
 // and the sum of squares over the values it has just written: after the last micro-batch of an
@@ -23,6 +24,9 @@
 #ifndef MA_ACCUM_UNROLL_ADD
 #define MA_ACCUM_UNROLL_ADD 4  // the same, add
 #endif
+#ifndef MA_ACCUM_UNROLL_ADD_SCAN
+#define MA_ACCUM_UNROLL_ADD_SCAN 8  // the same, add fused with the scan
+#endif
 #ifndef MA_ACCUM_BLOCKS_PER_CU
 #define MA_ACCUM_BLOCKS_PER_CU 1
 #endif
@@ -32,9 +36,9 @@
 
 namespace ma {
 
-template <bool FIRST>
+template <bool FIRST, bool SCAN>
 constexpr int accum_unroll() {
-  return FIRST ? MA_ACCUM_UNROLL_FIRST : MA_ACCUM_UNROLL_ADD;
+  return FIRST ? MA_ACCUM_UNROLL_FIRST : SCAN ? MA_ACCUM_UNROLL_ADD_SCAN : MA_ACCUM_UNROLL_ADD;
 }
 
 template <int GDT>
@@ -87,7 +91,7 @@ __global__ __launch_bounds__(kBlock) void accumulate_kernel(float* acc_, const v
                                                            uint32_t head, uint32_t vec,
                                                            uint64_t chunks, NormPartial* partials) {
   using GPacket = typename std::conditional<GDT == kF32, f32x4, u32x2>::type;
-  constexpr int kAccumUnroll = accum_unroll<FIRST>();
+  constexpr int kAccumUnroll = accum_unroll<FIRST, SCAN>();
   constexpr uint64_t kChunkGroups = uint64_t(kBlock) * kAccumUnroll;
   MA_GLOBAL float* acc = to_global(acc_);
   MA_GLOBAL const char* g = to_global(static_cast<const char*>(g_));
@@ -173,8 +177,9 @@ hipError_t launch_accumulate(float* acc, const void* g, int gdt, uint64_t n, uin
                              hipStream_t stream) {
   const bool scan = partials != nullptr;
   if (n == 0 && !scan) return hipSuccess;
-  const uint64_t kChunkElems =
-      uint64_t(kBlock) * 4 * (first ? accum_unroll<true>() : accum_unroll<false>());
+  const int unroll = first ? accum_unroll<true, false>()
+                           : scan ? accum_unroll<false, true>() : accum_unroll<false, false>();
+  const uint64_t kChunkElems = uint64_t(kBlock) * 4 * unroll;
   const uint64_t body = (vec && n > head) ? n - head : 0;
   const uint64_t chunks = vec ? (body + kChunkElems - 1) / kChunkElems : 0;
   uint64_t want = uint64_t(device_cus) * MA_ACCUM_BLOCKS_PER_CU;
