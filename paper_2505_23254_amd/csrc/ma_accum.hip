@@ -7,8 +7,10 @@
 // kernel; a persistent grid of one block per CU with the XCD-contiguous work assignment, which
 // keeps the eight XCDs at eight different places of the two buffers (with all blocks sweeping one
 // moving window the kernel was 25 % slower whenever both buffers lay in the same region of HBM).
-// Measured best depth: eight groups per lane in flight for the overwrite, four for the add, eight
-// for the add fused with the scan (whose fp64 arithmetic then overlaps more loads).
+// Measured best depth: eight groups per lane in flight for the overwrite, four for the add; fused
+// with the scan, whose fp64 arithmetic then overlaps more loads, twelve and eight (8B elements:
+// overwrite + scan 8.96 / 8.20 / 7.50 / 7.58 ms with 6 / 8 / 12 / 16 groups against 7.46 ms for the
+// plain overwrite; add + scan 12.93 / 12.64 / 12.555 / 12.76 ms with 4 / 6 / 8 / 10 against 12.55).
 //
 // The SCAN variant also runs the overflow check of Sec. IV-D / Algorithm 1 (with its fp32 mask)
 // and the sum of squares over the values it has just written: after the last micro-batch of an
@@ -27,6 +29,9 @@
 #ifndef MA_ACCUM_UNROLL_ADD_SCAN
 #define MA_ACCUM_UNROLL_ADD_SCAN 8  // the same, add fused with the scan
 #endif
+#ifndef MA_ACCUM_UNROLL_FIRST_SCAN
+#define MA_ACCUM_UNROLL_FIRST_SCAN 12  // the same, overwrite fused with the scan
+#endif
 #ifndef MA_ACCUM_BLOCKS_PER_CU
 #define MA_ACCUM_BLOCKS_PER_CU 1
 #endif
@@ -38,7 +43,8 @@ namespace ma {
 
 template <bool FIRST, bool SCAN>
 constexpr int accum_unroll() {
-  return FIRST ? MA_ACCUM_UNROLL_FIRST : SCAN ? MA_ACCUM_UNROLL_ADD_SCAN : MA_ACCUM_UNROLL_ADD;
+  return FIRST ? (SCAN ? MA_ACCUM_UNROLL_FIRST_SCAN : MA_ACCUM_UNROLL_FIRST)
+               : (SCAN ? MA_ACCUM_UNROLL_ADD_SCAN : MA_ACCUM_UNROLL_ADD);
 }
 
 template <int GDT>
@@ -177,8 +183,8 @@ hipError_t launch_accumulate(float* acc, const void* g, int gdt, uint64_t n, uin
                              hipStream_t stream) {
   const bool scan = partials != nullptr;
   if (n == 0 && !scan) return hipSuccess;
-  const int unroll = first ? accum_unroll<true, false>()
-                           : scan ? accum_unroll<false, true>() : accum_unroll<false, false>();
+  const int unroll = first ? (scan ? accum_unroll<true, true>() : accum_unroll<true, false>())
+                           : (scan ? accum_unroll<false, true>() : accum_unroll<false, false>());
   const uint64_t kChunkElems = uint64_t(kBlock) * 4 * unroll;
   const uint64_t body = (vec && n > head) ? n - head : 0;
   const uint64_t chunks = vec ? (body + kChunkElems - 1) / kChunkElems : 0;

@@ -44,7 +44,8 @@ def _micro_grad(n, seed, gdt, scale, device="cuda"):
 
 # ---- gradient accumulation --------------------------------------------------------------------------
 
-ACC_SIZES = [0, 1, 3, 4, 5, 1023, 1024, 4095, 4096, 4097, 8191, 8192, 8193, 16385, 100_003, (1 << 20) + 7]
+ACC_SIZES = [0, 1, 3, 4, 5, 1023, 1024, 4095, 4096, 4097, 8191, 8192, 8193, 12287, 12288, 12289, 16385, 100_003,
+             (1 << 20) + 7]
 
 
 @pytest.mark.parametrize("gdt", ["bf16", "f16", "f32"])
@@ -557,6 +558,19 @@ def test_accumulate_fused_with_scan(gdt):
             # the stand-alone scan of the same buffer agrees (same kernels' arithmetic, other order)
             ma.overflow_norm(acc, S, res, ws, index=1)
             assert abs(ma.read_result(res, 1)[1] - ss) <= 1e-12 * max(ss, 1e-300)
+    # one micro-batch per iteration: the overwrite itself is fused with the scan (its own tile size)
+    for n in [0, 1, 5, 4097, 12287, 12288, 12289, 24577, 100_003]:
+        for off_acc, off_g in ((0, 0), (1, 1), (2, 1)):
+            acc = torch.full((n + 4,), float("nan"), dtype=torch.float32, device="cuda")[off_acc:off_acc + n]
+            g = _micro_grad(n + 4, 3000 + n % 17, gdt, S)[off_g:off_g + n]
+            res = ma.new_result()
+            ma.grad_accumulate_scan(acc, g, True, S, res, ws)
+            ref = np.full(n, np.nan, np.float32)
+            oracle.grad_accumulate(ref, host_grad(g), gdt, first=True)
+            assert np.array_equal(host_f32(acc).view(np.uint32), ref.view(np.uint32)), (n, off_acc, off_g)
+            ov_ref, ss_ref = oracle.overflow_norm(ref, "f32", S)
+            ov, ss = ma.read_result(res)
+            assert ov == ov_ref == False and abs(ss - ss_ref) <= 1e-12 * max(ss_ref, 1e-300), (n, ss, ss_ref)
     # `first` with scan, scale taken from device memory, and an overflow entering with the micro-batch
     n = 50_001
     acc = torch.full((n,), float("nan"), dtype=torch.float32, device="cuda")
