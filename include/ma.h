@@ -172,6 +172,25 @@ int ma_plan_tensor(const ma_tensor* tensor_host, ma_dtype gdt, uint64_t* norm_it
 int ma_overflow_norm(const void* grad, ma_dtype gdt, size_t n, float loss_scale,
                      ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream);
 
+/* ma_overflow_norm for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid allocation.  The caller brings no workspace; the
+ * per-block partial results go to an array of MA_STATIC_SCRATCH_BYTES bytes that the library keeps
+ * in its own device image, one copy per GPU, from the first call on that GPU until the process
+ * ends.  The call allocates and frees nothing (its first call on a device looks up the array's
+ * address, nothing more).  Same kernels, same reduction order and so the same bits in *out_dev as
+ * ma_overflow_norm with a caller workspace.
+ *   - n > MA_STATIC_SCAN_MAX_ELEMS is rejected with MA_ERR_ARG before anything is launched (the
+ *     scan grid, and with it the scratch, is bounded by the device and not by n; the limit is far
+ *     above what the memory of one GPU can hold).
+ *   - Every call on one GPU uses that GPU's one array.  Nothing in it has to start at zero (each
+ *     launch overwrites the slots it later reads), so calls in sequence on one stream need no
+ *     clearing; calls that overlap in time on one GPU (two streams, two threads) race on it and
+ *     give wrong results.  Use ma_overflow_norm with one workspace per stream for those. */
+#define MA_STATIC_SCRATCH_BYTES (8192u * 16u)
+#define MA_STATIC_SCAN_MAX_ELEMS ((size_t)1 << 38)
+int ma_overflow_norm_static(const void* grad, ma_dtype gdt, size_t n, float loss_scale,
+                            ma_norm_result* out_dev, void* stream);
+
 /* Adds up `count` scan results (e.g. one per sub-group streamed through the optimizer-state
  * buffer, Sec. IV-C) in index order: overflow = OR, sumsq = fp64 sum.  out_dev may be one of
  * the inputs' neighbours but not an element of parts_dev.  count >= 1. */

@@ -84,6 +84,7 @@ def _load() -> ctypes.CDLL:
         "ma_step_scalars": ([vp, i64, f32, f32, vp], ctypes.c_int),
         "ma_plan_tensor": ([vp, i32, vp, vp, vp, vp, vp], ctypes.c_int),
         "ma_overflow_norm": ([vp, i32, sz, f32, vp, vp, sz, vp], ctypes.c_int),
+        "ma_overflow_norm_static": ([vp, i32, sz, f32, vp, vp], ctypes.c_int),
         "ma_norm_combine": ([vp, sz, vp, vp], ctypes.c_int),
         "ma_adamw_step": ([vp, vp, vp, vp, i32, vp, i32, sz, vp, i64, f32, f32, vp], ctypes.c_int),
         "ma_adamw_step_gated": ([vp, vp, vp, vp, i32, vp, i32, sz, vp, i64, f32, vp, f32, vp],
@@ -207,6 +208,14 @@ def overflow_norm(grad: torch.Tensor, loss_scale: float, out: torch.Tensor, ws: 
     _check(lib.ma_overflow_norm(_dev(grad, "grad"), _DT[grad.dtype],
                                 grad.numel() if n is None else n, loss_scale, _slot(out, index),
                                 _dev(ws, "ws"), ws.numel() * ws.element_size(), _stream(stream)))
+
+
+def overflow_norm_static(grad: torch.Tensor, loss_scale: float, out: torch.Tensor, index: int = 0,
+                         stream=None, n: Optional[int] = None) -> None:
+    """ma_overflow_norm_static: the scan with the library's own scratch (no workspace, no allocation)."""
+    _check(lib.ma_overflow_norm_static(_dev(grad, "grad"), _DT[grad.dtype],
+                                       grad.numel() if n is None else n, loss_scale, _slot(out, index),
+                                       _stream(stream)))
 
 
 def norm_combine(parts: torch.Tensor, count: int, out: torch.Tensor, index: int = 0,

@@ -1,10 +1,12 @@
 // C ABI of libma_step.so: argument checking, work-table construction, host scalars, launches.
 // See include/ma.h for the contract of every entry point.
 
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "../../include/ma.h"
@@ -17,6 +19,12 @@ static_assert(sizeof(ma_scaler_state) == sizeof(ma::ScalerState) && sizeof(ma_sc
 static_assert(sizeof(ma_scaler_config) == sizeof(ma::ScalerConfig), "scaler config layout");
 static_assert(int(MA_F32) == ma::kF32 && int(MA_BF16) == ma::kBF16 && int(MA_F16) == ma::kF16,
               "dtype codes");
+
+// Scratch of ma_overflow_norm_static: the per-block partial results of one scan launch, owned by
+// the library so that the call needs no workspace from the caller.  Every GPU the library runs on
+// holds its own copy at its own address until the process ends.  In host code this name only
+// identifies the symbol; the memory is reached through the address scratch_address() returns.
+static __device__ __align__(256) unsigned char scratch[ma::kMaxNormBlocks * sizeof(ma::NormPartial)];
 
 namespace {
 
@@ -40,22 +48,50 @@ bool dtype_ok(int dt) { return dt == MA_F32 || dt == MA_BF16 || dt == MA_F16; }
 size_t elem_bytes(int dt) { return dt == MA_F32 ? 4 : 2; }
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
 
-// Compute units of the current device (queried once per device index).
+constexpr int kMaxDevices = 64;
+
+// Compute units of the current device (queried once per device index; threads may race to fill a
+// slot, they all store the same value).
 int device_cus(int* out) {
-  static int cached[64] = {0};
+  static std::atomic<int> cached[kMaxDevices];
   int dev = 0;
   hipError_t e = hipGetDevice(&dev);
   if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
-  if (dev >= 0 && dev < 64 && cached[dev] > 0) {
-    *out = cached[dev];
-    return MA_OK;
+  const bool slot = dev >= 0 && dev < kMaxDevices;
+  if (slot) {
+    const int c = cached[dev].load(std::memory_order_relaxed);
+    if (c > 0) {
+      *out = c;
+      return MA_OK;
+    }
   }
   int cus = 0;
   e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
   if (e != hipSuccess) return fail_hip(e, "hipDeviceGetAttribute");
   if (cus <= 0) return fail(MA_ERR_HIP, "device reports %d compute units", cus);
-  if (dev >= 0 && dev < 64) cached[dev] = cus;
+  if (slot) cached[dev].store(cus, std::memory_order_relaxed);
   *out = cus;
+  return MA_OK;
+}
+
+// Device address of `scratch` on the current device.  Looked up once per device, with that device
+// current (each GPU has its own copy of the array), and kept; the lookup allocates nothing.
+int scratch_address(void** out) {
+  static std::mutex mu;
+  static void* addr[kMaxDevices] = {};
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return fail_hip(e, "hipGetDevice");
+  if (dev < 0 || dev >= kMaxDevices) return fail(MA_ERR_ARG, "device index %d is beyond the %d this library keeps scratch for", dev, kMaxDevices);
+  std::lock_guard<std::mutex> lock(mu);
+  if (addr[dev] == nullptr) {
+    void* p = nullptr;
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return fail_hip(e, "hipGetSymbolAddress(scratch)");
+    if (p == nullptr) return fail(MA_ERR_HIP, "hipGetSymbolAddress(scratch) returned a null address");
+    addr[dev] = p;
+  }
+  *out = addr[dev];
   return MA_OK;
 }
 
@@ -242,6 +278,9 @@ int multi_step(const ma_multi_plan* plan, const StepRequest& q, void* stream) {
   return step_common(nullptr, plan, plan->step_chunks, int(plan->sdt), plan->gdt, plan->pdt, q, stream);
 }
 
+// Passed as `ws` by the entry point that brings no workspace: never dereferenced.
+void* const kLibraryScratch = reinterpret_cast<void*>(uintptr_t(1));
+
 int norm_common(const ma::Desc* row, const ma_multi_plan* plan, uint64_t chunks, int gdt,
                 float loss_scale, const void* scaler, ma_norm_result* out_dev, void* ws,
                 size_t ws_bytes, void* stream) {
@@ -252,7 +291,12 @@ int norm_common(const ma::Desc* row, const ma_multi_plan* plan, uint64_t chunks,
   }
   if (!out_dev) return fail(MA_ERR_NULL, "out_dev is NULL");
   if (!aligned(out_dev, 8)) return fail(MA_ERR_ALIGN, "out_dev must be 8-byte aligned");
-  if (int rc = check_ws(ws, ws_bytes)) return rc;
+  if (ws == kLibraryScratch) {
+    // every argument has been checked; now the partials go to the library's own array
+    if (int rc = scratch_address(&ws)) return rc;
+  } else if (int rc = check_ws(ws, ws_bytes)) {
+    return rc;
+  }
   int cus = 0;
   if (int rc = device_cus(&cus)) return rc;
   const double inv = scaler ? 1.0 : 1.0 / (double(loss_scale) * double(loss_scale));
@@ -422,6 +466,17 @@ int ma_plan_tensor(const ma_tensor* t, ma_dtype gdt, uint64_t* norm_items, uint6
 int ma_overflow_norm(const void* grad, ma_dtype gdt, size_t n, float loss_scale,
                      ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream) {
   return flat_norm(grad, gdt, n, loss_scale, nullptr, false, out_dev, ws, ws_bytes, stream);
+}
+
+int ma_overflow_norm_static(const void* grad, ma_dtype gdt, size_t n, float loss_scale,
+                            ma_norm_result* out_dev, void* stream) {
+  static_assert(sizeof(scratch) == size_t(ma::kMaxNormBlocks) * sizeof(ma::NormPartial) &&
+                    sizeof(scratch) == MA_STATIC_SCRATCH_BYTES,
+                "one partial per block of the largest scan grid");
+  if (n > MA_STATIC_SCAN_MAX_ELEMS)
+    return fail(MA_ERR_ARG, "ma_overflow_norm_static: n = %zu exceeds the maximum of %zu elements", n,
+                size_t(MA_STATIC_SCAN_MAX_ELEMS));
+  return flat_norm(grad, gdt, n, loss_scale, nullptr, false, out_dev, kLibraryScratch, 0, stream);
 }
 
 int ma_norm_combine(const ma_norm_result* parts_dev, size_t count, ma_norm_result* out_dev,

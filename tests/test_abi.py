@@ -86,6 +86,14 @@ def test_scan_argument_errors():
     assert f(None, ma.MA_F16, 8, 1.0, A, A, ws, None) == ma.MA_ERR_NULL
     assert f(A + 1, ma.MA_F16, 8, 1.0, A, A, ws, None) == ma.MA_ERR_ALIGN
     assert f(A, ma.MA_F16, 8, 1.0, A + 4, A, ws, None) == ma.MA_ERR_ALIGN
+    # the variant with library-owned scratch checks the same arguments, and its size limit, first
+    g = ma.lib.ma_overflow_norm_static
+    assert g(A, ma.MA_BF16, 8, 1.0, None, None) == ma.MA_ERR_NULL
+    assert g(None, ma.MA_BF16, 8, 1.0, A, None) == ma.MA_ERR_NULL
+    assert g(A, 9, 8, 1.0, A, None) == ma.MA_ERR_DTYPE
+    assert g(A + 1, ma.MA_F16, 8, 1.0, A, None) == ma.MA_ERR_ALIGN
+    assert g(A, ma.MA_F16, 8, 0.0, A, None) == ma.MA_ERR_ARG
+    assert g(A, ma.MA_F16, (1 << 38) + 1, 1.0, A, None) == ma.MA_ERR_ARG and b"maximum" in ma.lib.ma_last_error()
     assert ma.lib.ma_norm_combine(A, 0, A + 64, None) == ma.MA_ERR_ARG
     assert ma.lib.ma_norm_combine(A, 4, A + 16, None) == ma.MA_ERR_ARG     # out inside parts
     assert ma.lib.ma_norm_combine(None, 4, A, None) == ma.MA_ERR_NULL
