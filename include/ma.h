@@ -145,7 +145,8 @@ float ma_clip_coef(double sumsq, float max_norm);
  *   {beta1, beta2, 1-beta1, 1-beta2, eps, lr/(1-beta1^step), 1/sqrt(1-beta2^step), lr*wd,
  *    clip_coef/loss_scale},
  * each evaluated in fp64 from the fp32 arguments and rounded once (the update kernels receive
- * exactly these).  Same argument checks as ma_adamw_step. */
+ * exactly these).  beta^step is an integer power by squaring carried in double-double arithmetic
+ * and rounded once to fp64 (the correctly rounded power, up to near-ties beyond 2^-95).  Same argument checks as ma_adamw_step. */
 int ma_step_scalars(const ma_hyper* hyper, int64_t step, float loss_scale, float clip_coef,
                     float out_host[9]);
 
@@ -279,7 +280,9 @@ int ma_overflow_norm_auto(const void* grad, ma_dtype gdt, size_t n, const ma_sca
                           ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream);
 
 /* ma_adamw_step_gated with the loss scale and the update number (scaler_dev->step + 1) read on the
- * device; the bias corrections are evaluated there in fp64.  A whole iteration
+ * device; the bias corrections are evaluated there in fp64 by the routine the host calls use
+ * (integer power by squaring in double-double arithmetic), so the step is bit-identical to
+ * ma_adamw_step_gated called with the same scale and update number.  A whole iteration
  *   ma_overflow_norm_auto -> ma_adamw_step_auto -> ma_scaler_update
  * needs no host round trip, whether or not the step is skipped. */
 int ma_adamw_step_auto(float* p32, float* m, float* v, const void* grad, ma_dtype gdt, void* p_lp,

@@ -472,8 +472,8 @@ __device__ __forceinline__ void step_pipeline(const StepScalars& s, Items& items
 // ---- what the kernel decides on the device ---------------------------------------------------------
 // Returns false when the step must not touch any buffer (Sec. III-C: the scan saw an overflow).
 //   * scaler state present: the loss scale and the update number (applied steps + 1) come from
-//     device memory, and the two bias-correction scalars are evaluated here, in fp64, exactly as
-//     the host does (pow, then one rounding to fp32 each);
+//     device memory, and the two bias-correction scalars are evaluated here, in fp64, by the same
+//     routine the host uses (pow_int, then one rounding to fp32 each): bit-identical scalars;
 //   * gate present: the unscale-and-clip factor follows from the scanned sum of squares with the
 //     same two roundings as the host path (clip coefficient to fp32, then c/S in fp64 to fp32).
 __device__ __forceinline__ bool prepare_step(const StepControl& ctl, StepScalars& s) {
@@ -482,9 +482,9 @@ __device__ __forceinline__ bool prepare_step(const StepControl& ctl, StepScalars
     loss_scale = ctl.scaler->scale;
     double bc1 = 1.0, bc2 = 1.0;
     if (ctl.bias_correction) {
-      const double t = static_cast<double>(ctl.scaler->step + 1);
-      bc1 = 1.0 - ::pow(static_cast<double>(s.beta1), t);
-      bc2 = 1.0 - ::pow(static_cast<double>(s.beta2), t);
+      const uint64_t t = static_cast<uint64_t>(ctl.scaler->step + 1);
+      bc1 = 1.0 - pow_int(static_cast<double>(s.beta1), t);
+      bc2 = 1.0 - pow_int(static_cast<double>(s.beta2), t);
     }
     s.step_size = static_cast<float>(static_cast<double>(ctl.lr) / bc1);
     s.inv_sqrt_bc2 = static_cast<float>(1.0 / __builtin_sqrt(bc2));

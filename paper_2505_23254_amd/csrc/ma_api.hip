@@ -119,8 +119,8 @@ ma::StepScalars host_scalars(const ma_hyper& h, int64_t step, float loss_scale, 
   const double b1 = h.beta1, b2 = h.beta2;
   double bc1 = 1.0, bc2 = 1.0;
   if (h.bias_correction) {
-    bc1 = 1.0 - std::pow(b1, double(step));
-    bc2 = 1.0 - std::pow(b2, double(step));
+    bc1 = 1.0 - ma::pow_int(b1, uint64_t(step));
+    bc2 = 1.0 - ma::pow_int(b2, uint64_t(step));
   }
   s.beta1 = h.beta1;
   s.beta2 = h.beta2;

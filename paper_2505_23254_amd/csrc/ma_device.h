@@ -151,6 +151,36 @@ struct StepControl {
   int32_t bias_correction;
 };
 
+// ---- beta^t for the bias corrections -----------------------------------------------------------
+// One routine for host and device, so that the scalars the device derives (update number read from
+// device memory) are bit-identical to those the host passes in kernel arguments.  Square-and-
+// multiply over the bits of t in double-double arithmetic (error-free products through fma): the
+// value is accurate to ~2^-95 before its one rounding to fp64, i.e. it is the correctly rounded
+// power except in astronomically rare near-tie cases, and it needs nothing but IEEE fp64
+// multiply, add and fma, which round the same way on both sides.
+struct DoubleDouble {
+  double hi, lo;
+};
+__host__ __device__ inline DoubleDouble dd_mul(DoubleDouble a, DoubleDouble b) {
+  const double p = a.hi * b.hi;
+  double e = __builtin_fma(a.hi, b.hi, -p);  // exact low part of the leading product
+  e = __builtin_fma(a.hi, b.lo, e);
+  e = __builtin_fma(a.lo, b.hi, e);
+  DoubleDouble r;
+  r.hi = p + e;
+  r.lo = e - (r.hi - p);
+  return r;
+}
+__host__ __device__ inline double pow_int(double base, uint64_t t) {
+  DoubleDouble r{1.0, 0.0}, b{base, 0.0};
+  while (t != 0) {
+    if (t & 1u) r = dd_mul(r, b);
+    t >>= 1;
+    if (t != 0) b = dd_mul(b, b);
+  }
+  return r.hi;
+}
+
 // ---- memory ------------------------------------------------------------------------------
 // Pointers read from a table in memory carry no address-space information, and the compiler
 // would fall back to flat addressing for them.  Every buffer of this library is global device

@@ -344,3 +344,45 @@ def bits16(t: torch.Tensor):
     if t.dtype == torch.float32:
         return t.detach().cpu().contiguous().numpy().copy()
     return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16).copy()
+
+
+# ----------------------------------------------------------------------------------------
+# Inputs at the edges of the fp32 range (for the oracle's exact-arithmetic pin and the GPU parity
+# tests alike; generation and library casts only).
+# ----------------------------------------------------------------------------------------
+import numpy as _np  # noqa: E402
+
+EXTREME_CASES = ("training", "subnormal", "subnormal_eps", "f16_subnormal_grads")
+
+
+def _log_uniform(rng, n, lo, hi, signed=True):
+    mag = _np.exp2(rng.uniform(lo, hi, n))
+    return (mag * (rng.choice([-1.0, 1.0], n) if signed else 1.0)).astype(_np.float32)
+
+
+def extreme_case(case: str, n: int, seed: int = 0):
+    """(p, m, v, grad bits, gdt, loss_scale, clip, eps) with magnitudes drawn log-uniformly:
+    "training": ordinary ranges; "subnormal": p, m, v and the unscaled gradient below 2^-126, so that
+    every intermediate of the step is subnormal or zero; "subnormal_eps": v = 0 and tiny gradients with
+    a subnormal eps, so that the denominator is subnormal and the quotient divides two subnormals;
+    "f16_subnormal_grads": fp16 gradients below 2^-14 at loss scale 1, subnormal second moments."""
+    rng = _np.random.default_rng(EXTREME_CASES.index(case) + 1 + 1000 * seed)
+    gdt, scale, clip, eps = "bf16", 1.0, 1.0, 1e-8
+    if case == "training":
+        p, m, v = _log_uniform(rng, n, -12, -2), _log_uniform(rng, n, -20, -8), _log_uniform(rng, n, -40, -16, False)
+        gf, scale, clip = _log_uniform(rng, n, -6, 8), 1024.0, 0.37
+    elif case == "subnormal":
+        p, m, v = (_log_uniform(rng, n, -149, -124), _log_uniform(rng, n, -149, -126),
+                   _log_uniform(rng, n, -149, -127, False))
+        gf, scale = _log_uniform(rng, n, -133, -110), 4.0
+    elif case == "subnormal_eps":
+        p, m, v = _log_uniform(rng, n, -30, -2), _log_uniform(rng, n, -149, -120), _np.zeros(n, _np.float32)
+        gf, eps = _log_uniform(rng, n, -133, -120), 1e-42
+        gf[::3] = 0.0
+    elif case == "f16_subnormal_grads":
+        p, m, v = _log_uniform(rng, n, -12, -2), _log_uniform(rng, n, -30, -14), _log_uniform(rng, n, -149, -120, False)
+        gf, gdt = _log_uniform(rng, n, -24, -14), "f16"
+    else:
+        raise KeyError(case)
+    g = bits16(torch.from_numpy(gf).to(torch.bfloat16 if gdt == "bf16" else torch.float16))
+    return p, m, v, g, gdt, scale, clip, eps

@@ -51,3 +51,63 @@ def assert_state_close(gpu, ref, what=""):
     assert np.array_equal(gpu["lp"], round_lp(gpu["p"], ref["pdt"])), "%s p_lp != RNE(p)" % what
     same = gpu["p"].view(np.uint32) == ref["p"].view(np.uint32)
     assert np.array_equal(gpu["lp"][same], ref["lp"][same]), "%s p_lp differs from oracle" % what
+
+
+
+class FullCompare:
+    """Element-by-element comparison of a whole device-resident state with the oracle, in slabs that
+    pass through page-locked host buffers: the state before the step (p, m, v, gradient) goes to the
+    host, the oracle updates it there in place, the result goes back to the device and is compared
+    with what the library wrote, as bit patterns.  A slab that is not bit-identical is compared again
+    on the host under the tolerance of assert_state_close, which also names the first offender."""
+
+    def __init__(self, slab: int, gdt: str, pdt: str, threads: int = 16):
+        self.slab, self.gdt, self.pdt, self.threads = slab, gdt, pdt, threads
+        graw = torch.float32 if gdt == "f32" else torch.int16
+        self.hp, self.hm, self.hv = (torch.empty(slab, dtype=torch.float32, pin_memory=True) for _ in range(3))
+        self.hg = torch.empty(slab, dtype=graw, pin_memory=True)
+        self.hl = torch.empty(slab, dtype=torch.int16, pin_memory=True)
+        self.dp, self.dm, self.dv = (torch.empty(slab, dtype=torch.float32, device="cuda") for _ in range(3))
+        self.dl = torch.empty(slab, dtype=torch.int16, device="cuda")
+        self.elements = 0          # compared so far
+        self.inexact_slabs = 0     # slabs that needed the tolerance
+
+    def _grad_host(self, g, a, b):
+        k = b - a
+        self.hg[:k].copy_(g[a:b] if self.gdt == "f32" else g[a:b].view(torch.int16))
+        raw = self.hg.numpy()[:k]
+        return raw if self.gdt == "f32" else raw.view(np.uint16)
+
+    def norm(self, g: torch.Tensor, scale: float):
+        """Oracle flag and sum of squares over a whole device gradient."""
+        ov, ss = False, 0.0
+        for a in range(0, g.numel(), self.slab):
+            o, s = oracle.overflow_norm(self._grad_host(g, a, min(g.numel(), a + self.slab)), self.gdt, scale,
+                                        nthreads=self.threads)
+            ov, ss = ov or o, ss + s
+        return ov, ss
+
+    def step(self, before, g, after, h, step, scale, clip, what=""):
+        """before: device (p, m, v) as they were; after: device (p, m, v, p_lp) as the library left them."""
+        n = g.numel()
+        assert all(t.numel() == n for t in (*before, *after))
+        for a in range(0, n, self.slab):
+            b = min(n, a + self.slab)
+            k = b - a
+            for dst, src in zip((self.hp, self.hm, self.hv), before):
+                dst[:k].copy_(src[a:b])
+            p, m, v = (t.numpy()[:k] for t in (self.hp, self.hm, self.hv))
+            lp = oracle.adamw_step(p, m, v, self._grad_host(g, a, b), self.gdt, self.pdt, h, step, scale, clip,
+                                   nthreads=self.threads)
+            self.hl.numpy()[:k] = lp.view(np.int16)
+            for dst, src in zip((self.dp, self.dm, self.dv, self.dl), (self.hp, self.hm, self.hv, self.hl)):
+                dst[:k].copy_(src[:k])
+            same = all(torch.equal(x[:k].view(torch.int32), y[a:b].view(torch.int32))
+                       for x, y in zip((self.dp, self.dm, self.dv), after[:3]))
+            same = same and torch.equal(self.dl[:k], after[3][a:b].view(torch.int16))
+            if not same:
+                self.inexact_slabs += 1
+                got = dict(p=host_f32(after[0][a:b]), m=host_f32(after[1][a:b]), v=host_f32(after[2][a:b]),
+                           lp=synth.bits16(after[3][a:b]))
+                assert_state_close(got, dict(p=p, m=m, v=v, lp=lp, pdt=self.pdt), "%s elements [%d, %d)" % (what, a, b))
+            self.elements += k

@@ -145,6 +145,32 @@ def test_host_step_scalars_match_oracle_bit_for_bit():
             assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), (lr, b1, b2, eps, wd, bc, step)
 
 
+def sweep_steps(count=4000, seed=5):
+    """Update numbers for the bias-correction sweeps: the small ones, decades up to 10^6 and their
+    neighbours, and seeded log-uniform draws in between."""
+    rng = np.random.default_rng(seed)
+    t = set(range(1, 300)) | {10 ** k + d for k in range(2, 7) for d in (-1, 0, 1)} | {2 ** k for k in range(1, 21)}
+    t |= set(int(x) for x in np.exp(rng.uniform(np.log(300), np.log(2e6), count)).astype(np.int64))
+    return sorted(t)
+
+
+SWEEP_BETAS = ((0.9, 0.999), (0.8, 0.95), (0.99, 0.9999))
+
+
+def test_host_bias_corrections_match_the_oracle_over_a_sweep_of_update_numbers():
+    """lr / (1 - beta1^t) and 1 / sqrt(1 - beta2^t): the library's integer power against the oracle's
+    library pow, as fp32 bit patterns, over thousands of update numbers."""
+    steps = sweep_steps()
+    assert len(steps) > 3000 and {1, 2, 1000, 10 ** 5, 10 ** 6} <= set(steps)
+    for b1, b2 in SWEEP_BETAS:
+        for lr in (1e-3, 3.7e-5):
+            h, ho = ma.hyper(lr, b1, b2, 1e-8, 0.01, 1), oracle.hyper(lr, b1, b2, 1e-8, 0.01, 1)
+            for t in steps:
+                got = np.array(ma.step_scalars(h, t), np.float32)
+                ref = oracle.step_scalars(ho, t)
+                assert np.array_equal(got.view(np.uint32), ref.view(np.uint32)), (b1, b2, lr, t)
+
+
 def _model_plan(p, m, v, g, lp, n, gbytes, norm_chunk_bytes, step_chunk_elems):
     """Independent model of the work split, from the contract in the header."""
     norm_head = ((16 - g % 16) % 16) // gbytes
@@ -375,3 +401,16 @@ int main(void) {
     assert int(f[3]) == lay.total_bytes and int(f[4]) == lay.uniform_bytes
     assert abs(float(f[5]) - 0.1) < 1e-7 and np.float32(float(f[6])) == np.float32(0.9)
     assert int(f[7]) == ma.MA_ERR_ARG and "step" in out[1]
+
+
+def test_gpu_tests_refuse_a_substituted_oracle(tmp_path):
+    """With MA_ORACLE_LIBRARY set every GPU-marked test fails in its set-up, before it touches a GPU."""
+    import shutil
+    import subprocess
+    import sys
+    alt = tmp_path / "liboracle_copy.so"
+    shutil.copy(os.path.join(ROOT, "oracle", "liboracle.so"), alt)
+    env = dict(os.environ, MA_ORACLE_LIBRARY=str(alt))
+    r = subprocess.run([sys.executable, "-m", "pytest", "tests/test_zz_no_alloc.py", "-m", "gpu", "-q",
+                        "-p", "no:cacheprovider"], cwd=ROOT, env=env, capture_output=True, text=True)
+    assert r.returncode != 0 and "MA_ORACLE_LIBRARY is set" in r.stdout

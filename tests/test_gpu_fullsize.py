@@ -1,11 +1,13 @@
 """GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
 
-Flat configurations up to 10^8 elements are compared element by element.  The 8B-shaped list
-(8.03e9 elements), the 14B-class list as 4 streamed sub-groups (12.57e9), a flat sub-group just
-beyond 2^31 elements, and the 8.03e9-element bf16-state and accumulation workloads are compared on
-samples the oracle can compute one by one -- the first and last 65,536 elements of every tensor,
-both sides of every sub-group cut and of element 2^32, and seeded random blocks -- while the
-overflow flag and the sum of squares are checked over ALL elements.
+Flat configurations up to 10^8 elements, the 8B-shaped list (8.03e9 elements, in the layout and
+placement the benchmark times) and all four sub-groups of the 14B-class list (12.57e9 elements) are
+compared with the oracle on EVERY element (the large ones in slabs streamed through the host).  The
+8B list in its other layout, a flat sub-group just beyond 2^31 elements, and the 8.03e9-element
+bf16-state and accumulation workloads are compared on samples the oracle can compute one by one --
+the first and last 65,536 elements of every tensor, both sides of every sub-group cut and of element
+2^32, and seeded random blocks -- while the overflow flag and the sum of squares are checked over
+ALL elements.
 """
 import numpy as np
 import pytest
@@ -13,12 +15,13 @@ import torch
 
 import oracle
 from paper_2505_23254_amd import hbm, synth
-from tests._util import SUMSQ_RTOL, assert_state_close, host_f32, host_grad, oracle_hyper
+from tests._util import SUMSQ_RTOL, FullCompare, assert_state_close, host_f32, host_grad, oracle_hyper
 
 pytestmark = pytest.mark.gpu
 
 EDGE = 65_536
 THREADS = 16
+SLAB = 1 << 27          # elements per slab of a full comparison
 ma = None
 
 
@@ -164,11 +167,59 @@ def _checksums_list(ls):
     return out
 
 
-@pytest.mark.parametrize("layout", ["streams", "tensor"])
+def test_llama3_8b_list_every_element():
+    """The benchmark workload itself, as the benchmark lays it out and places it (five flat streams cut
+    from a whole-device allocation, traffic split evenly over two HBM regions): 290 tensors,
+    8,030,257,152 elements, one scan launch and one gated update launch.  Flag and sum over all
+    elements, and EVERY element of p, m, v and the bf16 copy against the oracle: each work item is
+    processed exactly once, whichever block draws it."""
+    _need_gib(240)
+    shapes = synth.llama3_8b_shapes()
+    cfg = synth.FlatConfig("llama3_8b", 0, seed=3, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
+    device_arena = hbm.DeviceArena("cuda", reserve_gib=12)      # the checks below need temporaries
+    nbytes = synth.list_state_bytes(shapes, "streams")
+    window = device_arena.window(nbytes, synth.list_traffic(shapes, "streams"))
+    ls = synth.make_list(shapes, cfg, device="cuda", layout="streams", arena=window)
+    n = ls.total
+    assert n == 8_030_257_152 and ls.flat.p.numel() == n          # no padding between the views
+    # the state before the step is kept in the part of the allocation behind the window
+    end = window.data_ptr() - device_arena.buf.data_ptr() + nbytes
+    end = (end + hbm.ALIGN - 1) // hbm.ALIGN * hbm.ALIGN
+    if device_arena.nbytes - end < 12 * n:
+        pytest.skip("no room behind the state for a copy of p, m, v")
+    keep = [device_arena.buf[end + 4 * n * k:end + 4 * n * (k + 1)].view(torch.float32) for k in range(3)]
+    for dst, src in zip(keep, (ls.flat.p, ls.flat.m, ls.flat.v)):
+        dst.copy_(src)
+    full = FullCompare(SLAB, "bf16", "bf16", THREADS)
+    ov_ref, ss_ref = full.norm(ls.flat.g, 1.0)
+    c_ref = oracle.clip_coef(ss_ref, 1.0)
+    assert not ov_ref and 0.005 < c_ref < 0.02         # norm ~ 90
+    plan = ma.MultiPlan(ls.p, ls.m, ls.v, ls.g, ls.p_lp)
+    assert plan.plan.step_chunks >= 65536              # late work items are drawn on demand at this size
+    ws, res = ma.workspace(), ma.new_result()
+    ma.multi_overflow_norm(plan, 1.0, res, ws)
+    ma.multi_adamw_step_gated(plan, _hyper(cfg), 100, 1.0, res, 1.0)
+    ov, ss = ma.read_result(res)
+    assert not ov and abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref
+    assert np.float32(ma.clip_coef(ss, 1.0)) == c_ref
+    assert plan.table[:64].view(torch.int32).cpu().tolist() == [0] * 16
+    full.step(keep, ls.flat.g, (ls.flat.p, ls.flat.m, ls.flat.v, ls.flat.p_lp), oracle_hyper(cfg), 100, 1.0,
+              float(c_ref), "8B list")
+    assert full.elements == n
+    print("8B list: %d elements compared, %d slabs not bit-identical" % (full.elements, full.inexact_slabs))
+    # one NaN in a norm vector: the whole list is skipped, checked over every byte via checksums
+    sums = _checksums_list(ls)
+    ls.g[8].view(torch.int16)[4095] = 0x7FC0
+    ma.multi_overflow_norm(plan, 1.0, res, ws)
+    ma.multi_adamw_step_gated(plan, _hyper(cfg), 101, 1.0, res, 1.0)
+    assert ma.read_result(res)[0] is True
+    assert _checksums_list(ls) == sums
+
+
+@pytest.mark.parametrize("layout", ["tensor"])
 def test_llama3_8b_list_sampled(layout):
-    """The benchmark workload itself: 290 tensors, 8,030,257,152 elements, one scan launch and one
-    gated update launch; in the arena layout the benchmark times ("tensor": the five buffers of a
-    tensor adjacent) and with five flat buffers ("streams")."""
+    """The same list in its other layout ("tensor": the five buffers of a tensor adjacent), on
+    samples: tensor edges and seeded random blocks; flag and sum over all elements."""
     _need_gib(135)
     shapes = synth.llama3_8b_shapes()
     cfg = synth.FlatConfig("llama3_8b", 0, seed=3, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
@@ -209,10 +260,13 @@ def test_llama3_8b_list_sampled(layout):
     assert _checksums_list(ls) == sums
 
 
-def test_14b_class_four_sub_groups_sampled():
+def test_14b_class_four_sub_groups():
     """12,567,592,960 elements as 4 equal flat sub-groups (3,141,898,240 each, beyond 2^31) cut
-    without regard to tensor boundaries: 4 scans, 1 combine, 4 gated updates on one stream."""
-    _need_gib(210)
+    without regard to tensor boundaries.  First iteration: 4 scans, 1 combine, 4 gated updates back to
+    back on one stream, as the benchmark enqueues them, compared on samples.  Second iteration: the
+    same launches, each sub-group's update followed by a comparison of EVERY element of that sub-group
+    with the oracle.  Third iteration: the sub-groups as one-tensor lists, on samples."""
+    _need_gib(250)
     shapes = synth.qwen14b_class_shapes()
     total = sum(n for _, n in shapes)
     cfg = synth.FlatConfig("qwen14b_4sub", 0, seed=4, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
@@ -244,19 +298,40 @@ def test_14b_class_four_sub_groups_sampled():
     assert not ov and abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref
     assert np.float32(ma.clip_coef(ss, 1.0)) == c_ref
     assert_state_close(_sample_state(fl, ranges, "bf16"), before, "14B sub-groups sample")
-    # a second iteration with every sub-group prepared as a one-tensor list (the form in which a flat
+    # second iteration: every element of every sub-group
+    full = FullCompare(SLAB, "bf16", "bf16", THREADS)
+    keep = [torch.empty(sub, dtype=torch.float32, device="cuda") for _ in range(3)]
+    for k in range(4):
+        ma.overflow_norm(fl.g[k * sub:(k + 1) * sub], 1.0, parts, ws, index=k)
+    ma.norm_combine(parts, 4, res)
+    for k in range(4):
+        s = slice(k * sub, (k + 1) * sub)
+        for dst, src in zip(keep, (fl.p[s], fl.m[s], fl.v[s])):
+            dst.copy_(src)
+        ma.adamw_step_gated(fl.p[s], fl.m[s], fl.v[s], fl.g[s], fl.p_lp[s], _hyper(cfg), 101, 1.0, res, 1.0)
+        full.step(keep, fl.g[s], (fl.p[s], fl.m[s], fl.v[s], fl.p_lp[s]), oracle_hyper(cfg), 101, 1.0,
+                  float(c_ref), "14B sub-group %d" % k)
+    assert ma.read_result(res) == (False, ss)
+    assert full.elements == total
+    print("14B sub-groups: %d elements compared, %d slabs not bit-identical" % (full.elements, full.inexact_slabs))
+    del keep, full
+    torch.cuda.empty_cache()
+    before["lp"] = oracle.adamw_step(before["p"], before["m"], before["v"], g_s, "bf16", "bf16",
+                                     oracle_hyper(cfg), 101, 1.0, float(c_ref), nthreads=THREADS)
+    assert_state_close(_sample_state(fl, ranges, "bf16"), before, "14B sub-groups sample, second iteration")
+    # a third iteration with every sub-group prepared as a one-tensor list (the form in which a flat
     # sub-group gets its late work items drawn on demand)
     plans = []
     for k in range(4):
         s = slice(k * sub, (k + 1) * sub)
         plans.append(ma.MultiPlan([fl.p[s]], [fl.m[s]], [fl.v[s]], [fl.g[s]], [fl.p_lp[s]]))
     before["lp"] = oracle.adamw_step(before["p"], before["m"], before["v"], g_s, "bf16", "bf16",
-                                     oracle_hyper(cfg), 101, 1.0, float(c_ref), nthreads=THREADS)
+                                     oracle_hyper(cfg), 102, 1.0, float(c_ref), nthreads=THREADS)
     for k in range(4):
         ma.multi_overflow_norm(plans[k], 1.0, parts, ws, index=k)
     ma.norm_combine(parts, 4, res)
     for k in range(4):
-        ma.multi_adamw_step_gated(plans[k], _hyper(cfg), 101, 1.0, res, 1.0)
+        ma.multi_adamw_step_gated(plans[k], _hyper(cfg), 102, 1.0, res, 1.0)
     ov, ss2 = ma.read_result(res)
     assert not ov and ss2 == ss
     assert_state_close(_sample_state(fl, ranges, "bf16"), before, "14B sub-groups as one-tensor lists")

@@ -264,3 +264,79 @@ def test_8b_shaped_list_matches_printed_buffer_size(golden_dir):
     assert abs(total * 4 / 2 ** 30 - vals["flat_buffer_gib"]) < 0.01
     assert abs(total * 4 * 2.25 / 2 ** 30 - vals["peak_during_check_gib"]) < 0.02
     assert sum(n for _, n in synth.qwen14b_class_shapes()) == 12_567_592_960
+
+
+# ---- every rounding of the step, re-derived in exact rational arithmetic ------------------------
+# Each fp32 operation of the step returns the representable value nearest to the exact result (ties
+# to the even significand), subnormal results included; an addition exists only as the tail of a
+# fused multiply-add, which rounds once.  Below, the exact result of every operation is a Fraction
+# and `_rnd32` is that rounding written from its definition, so the comparison does not depend on
+# the host's floating-point unit, its flush-to-zero switches or its library.
+from fractions import Fraction
+from math import isqrt
+
+
+def _rnd32(x: Fraction) -> Fraction:
+    if x == 0:
+        return x
+    a = abs(x)
+    e = a.numerator.bit_length() - a.denominator.bit_length()
+    if Fraction(2) ** e > a:
+        e -= 1                                   # now 2^e <= a < 2^(e+1)
+    q = Fraction(2) ** (max(e, -126) - 23)       # spacing of fp32 values around a (subnormal: 2^-149)
+    k, r = divmod(a, q)
+    if 2 * r > q or (2 * r == q and k % 2 == 1):
+        k += 1
+    assert k * q < Fraction(2) ** 128            # the cases below stay finite
+    return k * q if x > 0 else -(k * q)
+
+
+def _sqrt32(x: Fraction) -> Fraction:
+    """Correctly rounded square root of an fp32 value: integer square root with 80 extra bits and a
+    sticky half-unit (the root of an fp32 value is never a rounding midpoint)."""
+    if x == 0:
+        return x
+    t = 200
+    n = x * Fraction(4) ** t
+    assert n.denominator == 1
+    s = isqrt(n.numerator)
+    exact = s * s == n.numerator
+    return _rnd32(Fraction(s, 2 ** t) if exact else Fraction(2 * s + 1, 2 ** (t + 1)))
+
+
+@pytest.mark.parametrize("case", synth.EXTREME_CASES)
+def test_every_rounding_against_exact_rational_arithmetic(case):
+    n, step = 1200, 7
+    p, m, v, g, gdt, scale, clip, eps = synth.extreme_case(case, n)
+    if gdt == "bf16":
+        w = (g.astype(np.uint32) << 16).view(np.float32)
+        assert case != "subnormal" or np.count_nonzero((g & 0x7F80) == 0) > n // 4     # bf16 subnormal patterns occur
+    else:
+        w = g.view(np.float16).astype(np.float32)
+        assert np.count_nonzero((g & 0x7C00) == 0) > n // 2                             # fp16 subnormal patterns
+    h = oracle.hyper(lr=1e-3, beta1=0.9, beta2=0.999, eps=eps, weight_decay=0.1)
+    s = [Fraction(float(x)) for x in oracle.step_scalars(h, step, scale, clip)]
+    b1, b2, omb1, omb2, eps_, step_size, isb2, decay, gscale = s
+    assert eps_ > 0
+    want = []
+    for i in range(n):
+        P, M, V, W = (Fraction(float(x[i])) for x in (p, m, v, w))
+        G = _rnd32(W * gscale)
+        M1 = _rnd32(b1 * M + _rnd32(omb1 * G))
+        V1 = _rnd32(b2 * V + _rnd32(omb2 * _rnd32(G * G)))
+        D = _rnd32(_sqrt32(V1) * isb2 + eps_)
+        U = _rnd32(M1 / D)
+        Q = _rnd32(-decay * P + P)
+        want.append((float(_rnd32(-step_size * U + Q)), float(M1), float(V1)))
+    want = np.array(want, np.float64)
+    lp = oracle.adamw_step(p, m, v, g, gdt, "bf16", h, step, scale, clip)
+    for k, (name, got) in enumerate((("p", p), ("m", m), ("v", v))):
+        bad = np.nonzero(got.astype(np.float64) != want[:, k])[0]
+        assert bad.size == 0, "%s[%d]: oracle %r, exact %r" % (name, bad[0], got[bad[0]], want[bad[0], k])
+    assert np.array_equal(lp, oracle.round_bf16(p))
+    if case.startswith("subnormal"):     # the case really lives where it claims to
+        tiny = float(np.finfo(np.float32).tiny)
+        assert np.count_nonzero((np.abs(m) < tiny) & (m != 0)) > n // 2
+    if case == "subnormal":
+        tiny = float(np.finfo(np.float32).tiny)
+        assert np.count_nonzero((np.abs(v) < tiny) & (v != 0)) > n // 2
