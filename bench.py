@@ -8,7 +8,12 @@ line: whole-job Gparam/s, the HBM roofline of the dominant (update) kernel measu
 stream events inside the timed region, and the CPU oracle timed on the host cores on a
 bounded sample of the same workload.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline] [--also none]
+
+With no --workload the line describes the 8B-shaped list (K timed steps) and carries, measured in the
+same process after the timed region: "also" = the other workloads below (their own short runs),
+roofline.frac_plain = the same kernel with the state in an ordinary allocation, and
+roofline.mix_ceiling_GBps = what a trivial kernel with the same stream mix reaches on the same buffers.
 
 Workloads: llama3_8b (default; 290-tensor Llama-3-8B-shaped list, 8.03e9 elements, bf16
 gradients, clip 1.0; --layout tensor|streams), flat_1e8, fp16_5e7, c1, qwen14b_4sub (12.57e9 elements as 4 flat
@@ -55,6 +60,16 @@ MEASURED_TRAFFIC = {      # workload: (bytes per launch, sources, their digest w
 }
 
 
+TRAFFIC_SOURCE = {
+    "llama3_8b": "profiles/hbm_traffic_counters__llama3_8b.txt",
+    "fp32grad_8b": "profiles/step_and_norm_multi_kernels__fp32grad_8b.txt",
+    "auto_fp16_8b": "profiles/step_and_norm_multi_kernels__auto_fp16_8b.txt",
+    "qwen14b_4sub": "profiles/step_and_norm_flat_kernels__qwen14b_4sub.txt",
+    "bf16_states_8b": "profiles/step_flat_kernel_bf16_states__bf16_states_8b.txt",
+    "accumulate_8b": "profiles/accumulate_kernel__accumulate_8b.txt",
+}
+
+
 def kernel_digest(sources=STEP_SOURCES):
     import hashlib
     h = hashlib.sha256()
@@ -79,18 +94,14 @@ def log(*a):
 class Workload:
     """Holds device state and enqueues one step; records (scan, update) event pairs."""
 
-    def __init__(self, name, ma, layout="streams", placement="region", rotate=1):
-        self.name, self.ma, self.layout, self.placement = name, ma, "flat", placement
-        # placement "region": the state is cut from one whole-device allocation at the offset
-        # that splits its traffic evenly over two of the three 96 GiB HBM regions (hbm.py);
-        # "plain": a fresh allocation of just the state's size, wherever the driver puts it
-        self.device_arena = None
-        if placement == "region":
-            try:
-                self.device_arena = hbm.DeviceArena("cuda")
-            except RuntimeError as e:      # e.g. another process holds most of the device
-                log("bench.py: whole-device arena not available (%s); falling back to a plain allocation" % e)
-                self.placement = placement = "plain"
+    def __init__(self, name, ma, layout="streams", arena=None, rotate=1):
+        # arena: an hbm.DeviceArena (placement "region": the state is cut from one whole-device
+        # allocation at the offset that splits its traffic evenly over two of the three 96 GiB HBM
+        # regions), or None (placement "plain": a fresh allocation of just the state's size, wherever
+        # the driver puts it)
+        self.name, self.ma, self.layout = name, ma, "flat"
+        self.placement = "region" if arena is not None else "plain"
+        self.device_arena = arena
         def place(nbytes, traffic):
             if self.device_arena is None:
                 return None
@@ -265,10 +276,23 @@ class Workload:
         self.t += 1
 
 
+def host_threads():
+    """Threads for the host baseline: this process's share of the box (its affinity mask, and the
+    thread count the box sets for worker pools), not every core the machine has."""
+    n = os.cpu_count() or 1
+    try:
+        n = min(n, len(os.sched_getaffinity(0)))
+    except AttributeError:
+        pass
+    env = os.environ.get("OMP_NUM_THREADS", "")
+    if env.isdigit() and int(env) > 0:
+        n = min(n, int(env))
+    return n
+
+
 def cpu_baseline(wl, sample_elems, passes):
     """The CPU oracle, as it stands, on the first `sample_elems` elements of the workload's state
-    (copied to the host), all host cores of this machine's share; also one thread on a smaller piece."""
-    import numpy as np
+    (copied to the host), on this process's share of the host cores; also one thread on a smaller piece."""
     import oracle
     c = wl.cfg
     if wl.kind == "multi":      # the list's first tensor (the embedding) is larger than any sample
@@ -281,11 +305,7 @@ def cpu_baseline(wl, sample_elems, passes):
     g = synth.bits16(src.g[:n])
     lp = synth.bits16(src.p_lp[:n])
     h = oracle.hyper(c.lr, c.beta1, c.beta2, c.eps, c.weight_decay, 1)
-    cores = min(16, os.cpu_count() or 1)
-    try:
-        cores = min(cores, len(os.sched_getaffinity(0)))
-    except AttributeError:
-        pass
+    cores = host_threads()
     oracle.optimizer_step(p, m, v, g, c.gdt, lp, c.pdt, h, 100, c.loss_scale, c.max_norm, nthreads=cores)
     t0 = time.perf_counter()
     for k in range(passes):
@@ -299,11 +319,118 @@ def cpu_baseline(wl, sample_elems, passes):
     dt1 = time.perf_counter() - t0
     return {
         "value": n / dt / 1e9, "unit": "Gparam/s", "cores": cores, "kind": "oracle",
+        "host_cores_visible": os.cpu_count(),
         "sample": "first %d elements of the workload, %d full passes (scan+gate+update) over %d "
-                  "threads; single thread on %d elements: %.4f Gparam/s"
-                  % (n, passes, cores, n1, n1 / dt1 / 1e9),
+                  "threads (this process's share of the host: the machine shows %s cores); single "
+                  "thread on %d elements: %.4f Gparam/s"
+                  % (n, passes, cores, os.cpu_count(), n1, n1 / dt1 / 1e9),
         "single_thread_value": n1 / dt1 / 1e9,
     }
+
+
+def run(wl, steps, warmup, events_in_region=True):
+    """W untimed and K timed steps of one workload; returns ms per step (wall clock between two device
+    synchronisations) and leaves per-step stream events in wl.events.  events_in_region=False: the
+    timed steps carry no events and the events come from a second pass of the same steps (for steps
+    of tens of microseconds, where recording three events per step costs as much as the step:
+    n = 2^20 measured 21 us per step without and 40 us with events)."""
+    for _ in range(warmup):
+        wl.step(False)
+    torch.cuda.synchronize()
+    wl.events = []
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        wl.step(events_in_region)
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / steps
+    if not events_in_region:
+        for _ in range(min(steps, 100)):
+            wl.step(True)
+        torch.cuda.synchronize()
+    return ms
+
+
+def summarise(wl, ma, ms_per_step, quiet=False):
+    """value (Gparam/s) and the roofline of the workload's dominant kernel from the stream events."""
+    first_ms = sum(e[0].elapsed_time(e[1]) for e in wl.events) / len(wl.events)
+    rest_ms = sum(e[1].elapsed_time(e[2]) for e in wl.events) / len(wl.events)
+    if not quiet:
+        log("2nd phase ms per step: " + " ".join("%.3f" % e[1].elapsed_time(e[2]) for e in wl.events))
+        log("1st phase ms per step: " + " ".join("%.3f" % e[0].elapsed_time(e[1]) for e in wl.events))
+    if wl.kind != "accum":
+        ov, ss = ma.read_result(wl.res)
+        if ov:
+            sys.exit("bench.py: unexpected overflow flag on clean synthetic gradients (%s)" % wl.name)
+    else:
+        ss = None
+    # launches of the dominant kernel in the second phase of a step, and what precedes them
+    launches = {"sub": 4, "accum": wl.micro - 1 if wl.kind == "accum" else 1}.get(wl.kind, 1)
+    passes = launches if wl.kind == "accum" else 1          # times the second phase sweeps all n elements
+    achieved = wl.step_bytes * wl.n * passes / (rest_ms * 1e-3) / 1e9
+    gdt_bytes = 4.0 if wl.cfg.gdt == "f32" else 2.0
+    if wl.kind == "accum":
+        first = {"kernel": "first micro-batch (overwrite)", "avg_ms": first_ms, "bytes_per_param": 6.0,
+                 "achieved": 6.0 * wl.n / (first_ms * 1e-3) / 1e9}
+        value = wl.n * wl.micro / (ms_per_step * 1e-3) / 1e9       # micro-batch elements accumulated
+        whole = (6.0 + 10.0 * (wl.micro - 1)) * wl.n / (ms_per_step * 1e-3) / 1e9
+    else:
+        first = {"kernel": "gradient scan (+ finalize)", "avg_ms": first_ms, "bytes_per_param": gdt_bytes,
+                 "achieved": gdt_bytes * wl.n / (first_ms * 1e-3) / 1e9}
+        value = wl.n / (ms_per_step * 1e-3) / 1e9
+        whole = (gdt_bytes + wl.step_bytes) * wl.n / (ms_per_step * 1e-3) / 1e9
+    traffic = measured_traffic(wl.name)
+    roofline = {
+        "bound": "hbm", "kernel": wl.kernel_label,
+        "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+        "traffic_source": (TRAFFIC_SOURCE.get(wl.name) if traffic is not None else
+                           "none: the kernel sources changed since the counters under profiles/ were taken"),
+        "algorithmic_bytes_per_launch": wl.step_bytes * wl.n / (4 if wl.kind == "sub" else 1),
+        "bytes_per_param": wl.step_bytes,
+        "params_per_launch": wl.n / (4 if wl.kind == "sub" else 1),
+        "avg_launch_ms": rest_ms / launches,
+        "first_phase": first,
+        "whole_step_GBps": whole,
+    }
+    return value, roofline, ss
+
+
+def mix_ceiling(wl, ma, reps=5):
+    """GB/s of the library's trivial same-mix kernel over the workload's own five flat buffers, where
+    they lie (destroys their contents): the ceiling of a 1:1 read/write mix for this placement."""
+    if wl.kind == "bf16":
+        bufs, per, item = (wl.bp, wl.bm, wl.bv, wl.bg, None), 14.0, 8192
+    else:
+        f = wl.state.flat if wl.kind in ("multi", "auto") else getattr(wl, "flat", None)
+        if f is None or f.g.element_size() != 2:
+            return None
+        bufs, per, item = (f.p, f.m, f.v, f.g, f.p_lp), 28.0, 4096
+    ma.probe_update_mix(*bufs)
+    best = 0.0
+    for _ in range(reps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        ma.probe_update_mix(*bufs)
+        b.record()
+        b.synchronize()
+        n = bufs[0].numel() // item * item
+        best = max(best, per * n / (a.elapsed_time(b) * 1e-3) / 1e9)
+    return best
+
+
+def release(wl):
+    import gc
+    for a in ("state", "plan", "flat", "flats", "raw", "bp", "bm", "bv", "bg", "acc", "device_arena"):
+        if hasattr(wl, a):
+            setattr(wl, a, None)
+    gc.collect()
+    torch.cuda.empty_cache()
+
+
+# The other workloads a default run reports under "also": (name, timed steps, warm-up steps, rotate).
+ALSO = (("c1", 400, 40, 32), ("flat_1e8", 100, 10, 1), ("fp16_5e7", 100, 10, 1), ("qwen14b_4sub", 8, 2, 1),
+        ("fp32grad_8b", 8, 2, 1), ("auto_fp16_8b", 8, 2, 1), ("bf16_states_8b", 10, 2, 1),
+        ("accumulate_8b", 5, 2, 1))
 
 
 def main():
@@ -311,9 +438,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="llama3_8b",
+    ap.add_argument("--workload", default=None,
                     choices=["llama3_8b", "fp32grad_8b", "flat_1e8", "fp16_5e7", "c1", "qwen14b_4sub",
-                             "bf16_states_8b", "accumulate_8b", "auto_fp16_8b"])
+                             "bf16_states_8b", "accumulate_8b", "auto_fp16_8b"],
+                    help="default: llama3_8b, followed by short runs of all the others (see --also)")
+    ap.add_argument("--also", default=None, choices=["all", "none"],
+                    help="after the timed region also run the other workloads, the plain-placement run and "
+                         "the mix-ceiling probe ('all': the default when no --workload is given)")
     ap.add_argument("--layout", default="streams", choices=["streams", "tensor"],
                     help="llama3_8b only: how the list's buffers lie in the state: 'streams' = five flat "
                          "buffers p|m|v|g|p_lp (default), 'tensor' = the five buffers of each tensor adjacent")
@@ -335,25 +466,33 @@ def main():
                  "--gpus must be 1 (no collectives or sharding are part of it)")
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
+    extras = (args.also or ("all" if args.workload is None else "none")) == "all"
+    name = args.workload or "llama3_8b"
 
     from paper_2505_23254_amd import binding as ma  # fails loudly if the library is not built
 
     torch.cuda.set_device(0)
+    arena, verify = None, None
+    if args.placement == "region":
+        try:
+            arena = hbm.DeviceArena("cuda")
+            _, total = torch.cuda.mem_get_info()
+            if arena.nbytes < 2 * hbm.REGION_BYTES + 16 * hbm.GIB:
+                log("bench.py: the arena (%.0f GiB of %.0f) does not reach the third HBM region; its offsets "
+                    "may not map onto the regions as assumed" % (arena.nbytes / hbm.GIB, total / hbm.GIB))
+            verify = arena.verify_regions(ma.probe_two_writes)
+            log("placement check (two write streams, GB/s): same region %s, different regions %s -> %s"
+                % (verify["same_GBps"], verify["cross_GBps"], "verified" if verify["verified"] else "NOT verified"))
+        except RuntimeError as e:      # e.g. another process holds most of the device
+            log("bench.py: whole-device arena not available (%s); falling back to a plain allocation" % e)
+            arena = None
     t_setup = time.perf_counter()
-    wl = Workload(args.workload, ma, args.layout, args.placement, max(1, args.rotate))
+    wl = Workload(name, ma, args.layout, arena, max(1, args.rotate))
     torch.cuda.synchronize()
     log("setup %.1f s: %s" % (time.perf_counter() - t_setup, wl.desc))
 
-    for _ in range(args.warmup):
-        wl.step(False)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        wl.step(True)
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
+    ms_per_step = run(wl, args.steps, args.warmup, events_in_region=wl.n >= 10 ** 9)
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
     if args.copy_calibration > 0:
         nb = args.copy_calibration
         if wl.device_arena is not None:      # the arena holds the device's memory: use its unused tail
@@ -373,31 +512,7 @@ def main():
         torch.cuda.synchronize()
         log("copy calibration: %d bytes read, %d bytes written" % (src.numel(), dst.numel()))
         del src, dst
-    first_ms = sum(e[0].elapsed_time(e[1]) for e in wl.events) / len(wl.events)
-    rest_ms = sum(e[1].elapsed_time(e[2]) for e in wl.events) / len(wl.events)
-    log("2nd phase ms per step: " + " ".join("%.3f" % e[1].elapsed_time(e[2]) for e in wl.events))
-    log("1st phase ms per step: " + " ".join("%.3f" % e[0].elapsed_time(e[1]) for e in wl.events))
-    if wl.kind != "accum":
-        ov, ss = ma.read_result(wl.res)
-        if ov:
-            sys.exit("bench.py: unexpected overflow flag on clean synthetic gradients")
-    else:
-        ss = None
-    # launches of the dominant kernel in the second phase of a step, and what precedes them
-    launches = {"sub": 4, "accum": wl.micro - 1 if wl.kind == "accum" else 1}.get(wl.kind, 1)
-    passes = launches if wl.kind == "accum" else 1          # times the second phase sweeps all n elements
-    achieved = wl.step_bytes * wl.n * passes / (rest_ms * 1e-3) / 1e9
-    gdt_bytes = 4.0 if wl.cfg.gdt == "f32" else 2.0
-    if wl.kind == "accum":
-        first = {"kernel": "first micro-batch (overwrite)", "avg_ms": first_ms, "bytes_per_param": 6.0,
-                 "achieved": 6.0 * wl.n / (first_ms * 1e-3) / 1e9}
-        value = wl.n * wl.micro / (ms_per_step * 1e-3) / 1e9       # micro-batch elements accumulated
-        whole = (6.0 + 10.0 * (wl.micro - 1)) * wl.n / (ms_per_step * 1e-3) / 1e9
-    else:
-        first = {"kernel": "gradient scan (+ finalize)", "avg_ms": first_ms, "bytes_per_param": gdt_bytes,
-                 "achieved": gdt_bytes * wl.n / (first_ms * 1e-3) / 1e9}
-        value = wl.n / (ms_per_step * 1e-3) / 1e9
-        whole = (gdt_bytes + wl.step_bytes) * wl.n / (ms_per_step * 1e-3) / 1e9
+    value, roofline, ss = summarise(wl, ma, ms_per_step)
     out = {
         "metric": "optimizer-step Gparam/s and achieved HBM GB/s (% of peak), 8B-shaped, 1 GPU",
         "value": value,
@@ -406,26 +521,63 @@ def main():
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": args.workload, "description": wl.desc, "elements": wl.n,
+        "config": {"workload": name, "description": wl.desc, "elements": wl.n,
                    "layout": wl.layout, "placement": wl.placement,
-                   "rotating_sets": len(getattr(wl, "flats", [None])),
+                   "placement_verified": None if verify is None or wl.placement != "region" else verify["verified"],
+                   "placement_check": verify,
+                   "rotating_sets": len(getattr(wl, "flats", None) or [None]),
                    "grad_dtype": wl.cfg.gdt, "param_copy_dtype": wl.cfg.pdt,
                    "max_norm": wl.cfg.max_norm, "loss_scale": wl.cfg.loss_scale,
                    "sumsq_last_step": ss},
-        "roofline": {
-            "bound": "hbm", "kernel": wl.kernel_label,
-            "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(args.workload),
-            "algorithmic_bytes_per_launch": wl.step_bytes * wl.n / (4 if wl.kind == "sub" else 1),
-            "bytes_per_param": wl.step_bytes,
-            "params_per_launch": wl.n / (4 if wl.kind == "sub" else 1),
-            "avg_launch_ms": rest_ms / launches,
-            "first_phase": first,
-            "whole_step_GBps": whole,
-        },
+        "roofline": roofline,
     }
     if not args.no_cpu_baseline and wl.kind in ("multi", "flat", "sub"):
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample, args.cpu_passes)
+    if extras:
+        t_extra = time.perf_counter()
+        ceil = mix_ceiling(wl, ma)
+        if ceil is not None:
+            roofline["mix_ceiling_GBps"] = ceil
+            roofline["frac_of_mix_ceiling"] = roofline["achieved"] / ceil
+            log("mix ceiling (%s placement): %.0f GB/s" % (wl.placement, ceil))
+        release(wl)
+        also = []
+        for other, steps, warmup, rotate in ALSO:
+            if other == name:
+                continue
+            w2 = Workload(other, ma, "streams", arena, rotate)
+            ms2 = run(w2, steps, warmup, events_in_region=w2.n >= 10 ** 9)
+            v2, r2, _ = summarise(w2, ma, ms2, quiet=True)
+            also.append({"workload": other, "description": w2.desc, "placement": w2.placement,
+                         "steps": steps, "ms_per_step": ms2, "value": v2,
+                         "kernel_events": "in the timed steps" if w2.n >= 10 ** 9 else "from a second pass",
+                         "unit": "Gparam/s" if w2.kind != "accum" else "G micro-batch elements/s",
+                         "roofline": {k: r2[k] for k in ("kernel", "achieved", "frac", "bytes_per_param",
+                                                         "avg_launch_ms", "first_phase", "traffic")}})
+            if w2.kind in ("bf16", "sub") or (w2.kind == "flat" and w2.n >= 10 ** 7):
+                also[-1]["roofline"]["mix_ceiling_GBps"] = mix_ceiling(w2, ma)
+            log("also %-15s %9.4f ms/step  %8.2f %s  dominant kernel %.4f ms = %.0f GB/s (%.1f %%)  mix ceiling %s"
+                % (other, ms2, v2, also[-1]["unit"], r2["avg_launch_ms"], r2["achieved"], 100 * r2["frac"],
+                   also[-1]["roofline"].get("mix_ceiling_GBps")))
+            release(w2)
+        out["also"] = also
+        if name == "llama3_8b" and arena is not None:
+            # the same list in an ordinary allocation: what a caller sees who cannot place the state
+            arena = None
+            import gc
+            gc.collect()
+            torch.cuda.empty_cache()
+            w3 = Workload(name, ma, args.layout, None, 1)
+            ms3 = run(w3, 8, 2)
+            v3, r3, _ = summarise(w3, ma, ms3, quiet=True)
+            roofline["frac_plain"] = r3["frac"]
+            roofline["plain"] = {"placement": "plain", "ms_per_step": ms3, "value": v3,
+                                 "achieved": r3["achieved"], "avg_launch_ms": r3["avg_launch_ms"],
+                                 "mix_ceiling_GBps": mix_ceiling(w3, ma)}
+            log("plain placement: %.3f ms/step, update %.0f GB/s (%.1f %%), mix ceiling %s GB/s"
+                % (ms3, r3["achieved"], 100 * r3["frac"], roofline["plain"]["mix_ceiling_GBps"]))
+            release(w3)
+        log("extras took %.1f s" % (time.perf_counter() - t_extra))
     print(json.dumps(out), flush=True)
 
 

@@ -22,12 +22,19 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
  *     enqueued on it; results are valid once the stream has been synchronised.  No entry point
  *     synchronises the device, except ma_multi_prepare (documented there).
- *   - Return value: MA_OK (0) or a negative ma_status.  On any error nothing has been launched
- *     and no buffer has been written.  ma_last_error() returns a thread-local message.
+ *   - Return value: MA_OK (0) or a negative ma_status.  Argument errors (MA_ERR_NULL, _DTYPE,
+ *     _ALIGN, _ARG) are found before anything is launched: no buffer has been written.  After
+ *     MA_ERR_HIP (the runtime refused a launch or a copy) part of the call's work may already be
+ *     enqueued, and the contents of the buffers the call writes are unspecified.
+ *     ma_last_error() returns a thread-local message.
  *   - n is a size_t element count; sub-groups beyond 2^31 elements are supported.
- *   - Buffers must not overlap each other.  Pointers must be aligned to their element size;
- *     16-byte alignment of every buffer enables the 128-bit path, anything else is handled by a
- *     scalar path with the same results.
+ *   - Buffers must not overlap each other: the update and accumulation calls and ma_multi_prepare
+ *     check the byte ranges they are given and return MA_ERR_ARG when two of them share a byte.
+ *     Pointers must be aligned to their element size; 16-byte alignment of every buffer enables the
+ *     128-bit path, anything else is handled by a scalar path with the same results.
+ *   - The entry points may be called from several host threads.  Work on different streams may
+ *     overlap in time as long as the calls share no buffer, workspace or plan (see
+ *     ma_multi_table_bytes).
  */
 #ifndef MA_STEP_H_
 #define MA_STEP_H_
@@ -295,8 +302,11 @@ int ma_adamw_step_auto(float* p32, float* m, float* v, const void* grad, ma_dtyp
 /* Bytes of device memory ma_multi_prepare needs for a list of `count` tensors: one row per tensor
  * and a 64-byte head of counters with which the blocks of an update launch share out the last part
  * of the work.  The library writes the table in ma_multi_prepare and the head during every
- * ma_multi_adamw_step* launch (which leaves it zeroed again); the caller never touches it.  As the
- * update launches of one plan write the same tensors, they must not overlap in time anyway. */
+ * ma_multi_adamw_step* launch (which leaves it zeroed again); the caller never touches it.
+ * NEVER have two update launches of one plan in flight at once (two streams without an ordering
+ * between them): they would share the counters, work items would be skipped or done twice, and they
+ * write the same tensors anyway.  The library cannot detect this.  Scan launches of one plan may
+ * overlap if they use different workspaces. */
 size_t ma_multi_table_bytes(size_t count);
 
 /* Validates list_host[0..count) (host array of device pointers; gradient dtype gdt, parameter
@@ -388,6 +398,25 @@ uint64_t ma_pinned_bytes(uint64_t request, int policy);
  * The caller frees it with ma_pinned_free.  These two calls need the HIP runtime. */
 int ma_pinned_alloc(size_t bytes, void** host_ptr_out);
 int ma_pinned_free(void* host_ptr);
+
+/* ---- measurement aids (not steps of the path; a benchmark runs them beside the real kernels) ------- */
+
+/* The update kernel's stream mix with trivial arithmetic.  state_elem_bytes == 4: per element reads
+ * a, b, c (4-byte elements) and d16 (2-byte), writes a, b, c and e16 (2-byte): 14 bytes in, 14 bytes
+ * out.  state_elem_bytes == 2 (states held in 16 bits): reads a, b, c, d16 (all 2-byte), writes a, b,
+ * c: 8 bytes in, 6 out; e16 is not used and may be NULL.  n elements (whole work items of 4096 resp.
+ * 8192 elements; the rest is left untouched).  All buffers 16-byte aligned device memory,
+ * overwritten with meaningless values.  What this reaches is the ceiling the memory system sustains
+ * for the step's read/write mix with the buffers where they are (Sec. II-A: the step is
+ * memory-bound). */
+int ma_probe_update_mix(void* a, void* b, void* c, const void* d16, void* e16, size_t n,
+                        int state_elem_bytes, void* stream);
+
+/* Two write-only streams of bytes_each bytes (whole multiples of 32 KiB are written), 16-byte aligned
+ * device memory.  Two streams inside one physical region of the HBM sustain less together than two
+ * streams in different regions, so timing this call at chosen offsets of a large allocation shows how
+ * the allocation maps onto the regions. */
+int ma_probe_two_writes(void* x, void* y, size_t bytes_each, void* stream);
 
 #ifdef __cplusplus
 }

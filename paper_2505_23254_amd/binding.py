@@ -117,6 +117,8 @@ def _load() -> ctypes.CDLL:
         "ma_adamw_step_auto": ([vp, vp, vp, vp, i32, vp, i32, sz, vp, vp, vp, f32, vp],
                                ctypes.c_int),
         "ma_multi_overflow_norm_auto": ([vp, vp, vp, vp, sz, vp], ctypes.c_int),
+        "ma_probe_update_mix": ([vp, vp, vp, vp, vp, sz, i32, vp], ctypes.c_int),
+        "ma_probe_two_writes": ([vp, vp, sz, vp], ctypes.c_int),
         "ma_multi_adamw_step_auto": ([vp, vp, vp, vp, f32, vp], ctypes.c_int),
     }
     for name, (args, res) in sig.items():
@@ -430,6 +432,29 @@ def multi_adamw_step_auto(plan: MultiPlan, h: Hyper, scaler: torch.Tensor, gate:
                           max_norm: float, index: int = 0, stream=None) -> None:
     _check(lib.ma_multi_adamw_step_auto(ctypes.byref(plan.plan), ctypes.byref(h), _scaler(scaler),
                                         _slot(gate, index), max_norm, _stream(stream)))
+
+
+# ---- measurement aids ---------------------------------------------------------------------------------
+
+def probe_update_mix(a, b, c, d16, e16=None, stream=None) -> None:
+    """ma_probe_update_mix over the buffers of a state (contents destroyed): 14 B in / 14 B out per
+    element for 4-byte a, b, c (e16 required), 8 in / 6 out for 2-byte a, b, c."""
+    n, eb = a.numel(), a.element_size()
+    if not (b.numel() == n and c.numel() == n and d16.numel() == n and (e16 is None or e16.numel() == n)):
+        raise ValueError("the buffers must have the same number of elements")
+    if eb not in (2, 4) or b.element_size() != eb or c.element_size() != eb or d16.element_size() != 2 or \
+            (eb == 4 and (e16 is None or e16.element_size() != 2)):
+        raise TypeError("a, b, c hold 4-byte (with a 2-byte e16) or 2-byte elements, d16 2-byte elements")
+    _check(lib.ma_probe_update_mix(_dev(a, "a"), _dev(b, "b"), _dev(c, "c"), _dev(d16, "d16"),
+                                   _dev(e16, "e16"), n, eb, _stream(stream)))
+
+
+def probe_two_writes(x: torch.Tensor, y: torch.Tensor, stream=None) -> None:
+    """ma_probe_two_writes over two equally large device buffers (contents destroyed)."""
+    nb = x.numel() * x.element_size()
+    if y.numel() * y.element_size() != nb:
+        raise ValueError("the two buffers must be equally large")
+    _check(lib.ma_probe_two_writes(_dev(x, "x"), _dev(y, "y"), nb, _stream(stream)))
 
 
 # ---- host side: parameter buffer pool and pinned sizes ------------------------------------------------

@@ -599,7 +599,9 @@ static hipError_t launch_step_typed(const Desc* row_host, const Desc* table_dev,
                                     uint64_t chunks, const StepScalars& s, const StepControl& ctl,
                                     StepQueue* queue, int device_cus, hipStream_t stream) {
   // A persistent grid must be fully resident: blocks that wait for a slot would run alone at the
-  // end.  So: no more blocks per compute unit than the kernel's occupancy allows.
+  // end.  So: no more blocks per compute unit than the kernel's occupancy allows.  Queried once per
+  // process and instantiation (thread-safe static initialisation), for the device current at that
+  // moment: all GPUs of one process are taken to be the same model.
   static const int occ_flat = resident_blocks_per_cu(step_flat_kernel<SDT, GDT, PDT>);
   static const int occ_multi = resident_blocks_per_cu(step_multi_kernel<SDT, GDT, PDT>);
   const int occ = row_host ? occ_flat : occ_multi;

@@ -1,6 +1,7 @@
 // C ABI of libma_step.so: argument checking, work-table construction, host scalars, launches.
 // See include/ma.h for the contract of every entry point.
 
+#include <algorithm>
 #include <atomic>
 #include <cmath>
 #include <cstdarg>
@@ -136,6 +137,36 @@ ma::StepScalars host_scalars(const ma_hyper& h, int64_t step, float loss_scale, 
 
 uint64_t ceil_div(uint64_t a, uint64_t b) { return (a + b - 1) / b; }
 
+// A buffer named in a call, as a byte range.
+struct Range {
+  uintptr_t lo, hi;
+  uint32_t owner;  // index of the tensor it belongs to (lists)
+};
+Range range_of(const void* p, uint64_t bytes, uint32_t owner = 0) {
+  const uintptr_t a = reinterpret_cast<uintptr_t>(p);
+  return Range{a, a + bytes, owner};
+}
+// True when two of the (non-empty) ranges share a byte; a and b receive their positions in `r`.
+bool any_overlap(std::vector<Range>& r, const Range** a, const Range** b) {
+  std::sort(r.begin(), r.end(), [](const Range& x, const Range& y) { return x.lo < y.lo; });
+  for (size_t i = 1; i < r.size(); ++i) {
+    if (r[i].lo < r[i - 1].hi) {
+      *a = &r[i - 1];
+      *b = &r[i];
+      return true;
+    }
+  }
+  return false;
+}
+// The buffers of one row: p, m, v (sb bytes per element), the gradient, the optional 16-bit copy.
+void row_ranges(const ma::Desc& d, int gdt, size_t sb, uint32_t owner, std::vector<Range>& out) {
+  out.push_back(range_of(d.p, d.n * sb, owner));
+  out.push_back(range_of(d.m, d.n * sb, owner));
+  out.push_back(range_of(d.v, d.n * sb, owner));
+  out.push_back(range_of(d.g, d.n * elem_bytes(gdt), owner));
+  if (d.lp) out.push_back(range_of(d.lp, d.n * 2, owner));
+}
+
 // Fills the alignment-dependent fields of a row and returns its work-item counts.
 // Returns a negative status if a pointer is not aligned to its element size.
 int plan_row(ma::Desc& d, int gdt, bool has_lp, uint64_t* norm_chunks, uint64_t* step_chunks,
@@ -268,6 +299,13 @@ int flat_step(void* p, void* m, void* v, const void* grad, ma_dtype gdt, void* p
   d.n = n;
   uint64_t nc = 0, sc = 0;
   if (int rc = plan_row(d, gdt, p_lp != nullptr, &nc, &sc, sdt == MA_F32 ? 4 : 2)) return rc;
+  {
+    std::vector<Range> r;
+    row_ranges(d, gdt, sdt == MA_F32 ? 4 : 2, 0, r);
+    const Range *a = nullptr, *b = nullptr;
+    if (any_overlap(r, &a, &b))
+      return fail(MA_ERR_ARG, "buffers overlap: [%p, %p) and [%p, %p)", (void*)a->lo, (void*)a->hi, (void*)b->lo, (void*)b->hi);
+  }
   return step_common(&d, nullptr, sc, sdt, gdt, p_lp ? int(pdt) : ma::kNoLp, q, stream);
 }
 
@@ -340,6 +378,8 @@ int prepare_common(size_t count, ma_dtype gdt, int pdt, int sdt, void* table_dev
 
   std::vector<ma::Desc> rows;
   rows.reserve(count);
+  std::vector<Range> ranges;
+  ranges.reserve(5 * count);
   uint64_t norm_total = 0, step_total = 0, elems = 0;
   int has_lp = -1;
   for (size_t i = 0; i < count; ++i) {
@@ -357,12 +397,19 @@ int prepare_common(size_t count, ma_dtype gdt, int pdt, int sdt, void* table_dev
       std::snprintf(msg, sizeof(msg), "%s", g_error);
       return fail(rc, "tensor %zu: %s", i, msg);
     }
+    row_ranges(d, gdt, sdt == MA_F32 ? 4 : 2, uint32_t(i), ranges);
     d.norm_chunk0 = norm_total;
     d.step_chunk0 = step_total;
     norm_total += nc;
     step_total += sc;
     elems += d.n;
     rows.push_back(d);
+  }
+  {
+    const Range *a = nullptr, *b = nullptr;
+    if (any_overlap(ranges, &a, &b))
+      return fail(MA_ERR_ARG, "buffers overlap: tensor %u [%p, %p) and tensor %u [%p, %p)", a->owner, (void*)a->lo,
+                  (void*)a->hi, b->owner, (void*)b->lo, (void*)b->hi);
   }
   {
     // the counters (all zero), then the rows, in one copy
@@ -583,6 +630,11 @@ int accumulate_common(float* acc32, const void* grad, ma_dtype gdt, size_t n, in
   const size_t gb = elem_bytes(gdt);
   if (!aligned(acc32, 4) || !aligned(grad, gb))
     return fail(MA_ERR_ALIGN, "acc32 / grad not aligned to their element size");
+  if (n > 0) {
+    std::vector<Range> r{range_of(acc32, uint64_t(n) * 4), range_of(grad, uint64_t(n) * gb)};
+    const Range *a = nullptr, *b = nullptr;
+    if (any_overlap(r, &a, &b)) return fail(MA_ERR_ARG, "acc32 and grad overlap");
+  }
   const uint32_t h = uint32_t(((16 - (reinterpret_cast<uintptr_t>(acc32) % 16)) % 16) / 4);
   const uint32_t vec = ((reinterpret_cast<uintptr_t>(grad) + uint64_t(h) * gb) % (4 * gb)) == 0;
   int cus = 0;

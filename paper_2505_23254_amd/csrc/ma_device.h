@@ -36,6 +36,9 @@ constexpr int kNoLp = 3;  // update kernel variant that writes no low-precision 
 #ifndef MA_NORM_MAP
 #define MA_NORM_MAP 0  // work-item assignment of the scan kernel (see WorkIter)
 #endif
+#ifndef MA_NORM_KEEP_MIB
+#define MA_NORM_KEEP_MIB 320  // gradient bytes (MiB) the scan leaves in the memory-side cache for the update kernel
+#endif
 #ifndef MA_STEP_UNROLL_BF16
 #define MA_STEP_UNROLL_BF16 6  // 8-element groups per lane and tile when p, m, v are held in bf16
 #endif
@@ -204,6 +207,19 @@ __device__ __forceinline__ T ld_stream(MA_GLOBAL const T* p) {
 #else
   return *p;
 #endif
+}
+// A load whose line may stay in the caches: for data that a later kernel reads again.
+template <class T>
+__device__ __forceinline__ T ld_keep(MA_GLOBAL const T* p) {
+  return *p;
+}
+template <bool KEEP, class T>
+__device__ __forceinline__ T ld_scan(MA_GLOBAL const T* p) {
+  if constexpr (KEEP) {
+    return ld_keep(p);
+  } else {
+    return ld_stream(p);
+  }
 }
 template <class T>
 __device__ __forceinline__ void st_stream(MA_GLOBAL T* p, T x) {

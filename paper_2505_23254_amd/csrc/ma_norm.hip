@@ -13,6 +13,18 @@
 // Per block: xor-shuffle tree inside each wave, four wave results through LDS, one partial
 // per block in the caller's workspace.  A one-block finalize kernel adds the partials in index
 // order.  No floating-point atomics anywhere: the result is bit-identical from run to run.
+//
+// The update kernel reads the same gradient again right after this pass.  Measured on MI355X, a
+// line loaded WITHOUT the non-temporal hint stays in the 256 MB memory-side cache, the update
+// kernel's own non-temporal traffic does not push it out, and the update then runs 6 % faster when
+// the whole gradient was kept (n = 1e8: 0.448 -> 0.423 ms; n = 5e7: 0.229 -> 0.217 ms; scan + update
+// 204 -> 214 and 196 -> 203 Gparam/s).  Keeping costs the scan about 10 % on the bytes it keeps, so
+// the scan keeps only about what the cache can hold: `keep_of_64` of every 64 work items, chosen on
+// the host (all of them for gradients up to MA_NORM_KEEP_MIB, a proportional share above, none once
+// the share drops below one in eight: 8.03e9 elements gain nothing and a scan with 1/64 kept was
+// 9 % slower there).  The kept items are spread evenly over the gradient, so every part of the update
+// launch gains alike, and evenly over the blocks of this launch, so that none of them lags
+// (n = 2e8: scan + update 0.954 -> 0.923 ms; 4e8: 1.888 -> 1.849; 1e9: 4.685 -> 4.665).
 
 #include "ma_internal.h"
 
@@ -20,7 +32,7 @@ namespace ma {
 
 // One work item: kNormChunkBytes of the row's 16-byte-aligned body; item 0 also takes the
 // unaligned head elements, the last item the ragged tail.
-template <int GDT>
+template <int GDT, bool KEEP>
 __device__ __forceinline__ void norm_chunk(NormAcc<GDT>& acc, const void* g_, uint64_t n,
                                            uint32_t head, uint64_t lc) {
   MA_GLOBAL const char* g = to_global(static_cast<const char*>(g_));
@@ -41,14 +53,14 @@ __device__ __forceinline__ void norm_chunk(NormAcc<GDT>& acc, const void* g_, ui
   if (v0 + kChunkVecs <= nvec) {
     u32x4 w[kNormUnroll];
 #pragma unroll
-    for (int u = 0; u < kNormUnroll; ++u) w[u] = ld_stream(base + v0 + tid + uint64_t(u) * kBlock);
+    for (int u = 0; u < kNormUnroll; ++u) w[u] = ld_scan<KEEP>(base + v0 + tid + uint64_t(u) * kBlock);
 #pragma unroll
     for (int u = 0; u < kNormUnroll; ++u) acc.vec(w[u]);
   } else {
 #pragma unroll
     for (int u = 0; u < kNormUnroll; ++u) {
       const uint64_t vi = v0 + tid + uint64_t(u) * kBlock;
-      if (vi < nvec) acc.vec(ld_stream(base + vi));
+      if (vi < nvec) acc.vec(ld_scan<KEEP>(base + vi));
     }
     // this is the row's last item: fewer than kPerVec elements remain after the last vector
     const uint64_t t0 = uint64_t(head) + nvec * kPerVec;
@@ -56,13 +68,26 @@ __device__ __forceinline__ void norm_chunk(NormAcc<GDT>& acc, const void* g_, ui
   }
 }
 
+// c is uniform across the block, so this is a scalar branch between two copies of the loop body.
+template <int GDT>
+__device__ __forceinline__ void norm_item(NormAcc<GDT>& acc, const void* g, uint64_t n, uint32_t head,
+                                          uint64_t lc, uint64_t c, uint32_t keep_of_64) {
+  // block b sees items b, b + G, b + 2G, ... (G a multiple of 64 on every device of interest): adding
+  // the round number makes every block walk through all 64 residues
+  if (((c + c / gridDim.x) & 63u) < keep_of_64) {
+    norm_chunk<GDT, true>(acc, g, n, head, lc);
+  } else {
+    norm_chunk<GDT, false>(acc, g, n, head, lc);
+  }
+}
+
 // Flat sub-group: the row travels in the kernel arguments.
 template <int GDT>
-__global__ __launch_bounds__(kBlock) void norm_flat_kernel(Desc row, uint64_t chunks,
+__global__ __launch_bounds__(kBlock) void norm_flat_kernel(Desc row, uint64_t chunks, uint32_t keep_of_64,
                                                           NormPartial* partials) {
   NormAcc<GDT> acc;
   for (WorkIter<MA_NORM_MAP> w(chunks); w.c < w.end; w.c += w.stride) {
-    norm_chunk<GDT>(acc, row.g, row.n, row.norm_head, w.c);
+    norm_item<GDT>(acc, row.g, row.n, row.norm_head, w.c, w.c, keep_of_64);
   }
   norm_block_finish<GDT>(acc, partials);
 }
@@ -87,14 +112,14 @@ __device__ __forceinline__ uint32_t find_row(const Desc* table, uint32_t lo, uin
 template <int GDT>
 __global__ __launch_bounds__(kBlock) void norm_multi_kernel(const Desc* __restrict__ table,
                                                            uint32_t rows, uint64_t chunks,
-                                                           NormPartial* partials) {
+                                                           uint32_t keep_of_64, NormPartial* partials) {
   NormAcc<GDT> acc;
   uint32_t r = 0;
   for (WorkIter<MA_NORM_MAP> w(chunks); w.c < w.end; w.c += w.stride) {
     const uint64_t c = w.c;
     r = find_row(table, r, rows, c);
     const Desc* d = table + r;
-    norm_chunk<GDT>(acc, d->g, d->n, d->norm_head, c - d->norm_chunk0);
+    norm_item<GDT>(acc, d->g, d->n, d->norm_head, c - d->norm_chunk0, c, keep_of_64);
   }
   norm_block_finish<GDT>(acc, partials);
 }
@@ -175,17 +200,21 @@ hipError_t launch_norm(const Desc* row_host, const Desc* table_dev, uint32_t row
   uint64_t want = uint64_t(device_cus) * MA_NORM_BLOCKS_PER_CU;
   if (want > kMaxNormBlocks) want = kMaxNormBlocks;
   const uint32_t grid = static_cast<uint32_t>(chunks < want ? (chunks ? chunks : 1) : want);
+  // how many of every 64 work items keep their lines in the memory-side cache for the update kernel
+  const uint64_t bytes = chunks * kNormChunkBytes, cap = uint64_t(MA_NORM_KEEP_MIB) << 20;
+  uint32_t keep = bytes <= cap ? 64u : static_cast<uint32_t>(cap * 64 / bytes);
+  if (keep < 8) keep = 0;
   if (row_host) {
     switch (gdt) {
-      case kBF16: norm_flat_kernel<kBF16><<<grid, kBlock, 0, stream>>>(*row_host, chunks, partials); break;
-      case kF16: norm_flat_kernel<kF16><<<grid, kBlock, 0, stream>>>(*row_host, chunks, partials); break;
-      default: norm_flat_kernel<kF32><<<grid, kBlock, 0, stream>>>(*row_host, chunks, partials); break;
+      case kBF16: norm_flat_kernel<kBF16><<<grid, kBlock, 0, stream>>>(*row_host, chunks, keep, partials); break;
+      case kF16: norm_flat_kernel<kF16><<<grid, kBlock, 0, stream>>>(*row_host, chunks, keep, partials); break;
+      default: norm_flat_kernel<kF32><<<grid, kBlock, 0, stream>>>(*row_host, chunks, keep, partials); break;
     }
   } else {
     switch (gdt) {
-      case kBF16: norm_multi_kernel<kBF16><<<grid, kBlock, 0, stream>>>(table_dev, rows, chunks, partials); break;
-      case kF16: norm_multi_kernel<kF16><<<grid, kBlock, 0, stream>>>(table_dev, rows, chunks, partials); break;
-      default: norm_multi_kernel<kF32><<<grid, kBlock, 0, stream>>>(table_dev, rows, chunks, partials); break;
+      case kBF16: norm_multi_kernel<kBF16><<<grid, kBlock, 0, stream>>>(table_dev, rows, chunks, keep, partials); break;
+      case kF16: norm_multi_kernel<kF16><<<grid, kBlock, 0, stream>>>(table_dev, rows, chunks, keep, partials); break;
+      default: norm_multi_kernel<kF32><<<grid, kBlock, 0, stream>>>(table_dev, rows, chunks, keep, partials); break;
     }
   }
   hipError_t e = hipGetLastError();

@@ -56,6 +56,40 @@ class DeviceArena:
         start = start // ALIGN * ALIGN
         return self.buf[start:start + nbytes]
 
+    def verify_regions(self, two_writes, gib_each: int = 2, reps: int = 3, margin: float = 1.08) -> dict:
+        """Checks, by timing, that byte offset x of this allocation lies in region x // 96 GiB.
+
+        `two_writes(x, y)` enqueues a kernel that writes the two uint8 views once (the library's
+        ma_probe_two_writes).  Pairs of windows that the linear map puts into ONE region must be slower
+        than pairs it puts into two different regions, by at least `margin`.  Run it before the arena
+        holds data: the windows are overwritten.  Returns {"verified", "same_GBps", "cross_GBps"}."""
+        nb = gib_each * GIB
+        last = (self.nbytes - nb) // GIB                 # last whole-GiB offset a window can start at
+        inside = lambda r: [o for o in (96 * r + 8, 96 * r + 56) if o + gib_each <= 96 * (r + 1) and o <= last]
+        offs = [inside(r) for r in range(3)]
+        same = [tuple(o) for o in offs if len(o) == 2]
+        cross = [(offs[r][0], offs[r + 1][0]) for r in range(2) if offs[r] and offs[r + 1]]
+        cross += [(offs[r][1], offs[r + 1][1]) for r in range(2) if len(offs[r]) == 2 and len(offs[r + 1]) == 2]
+        if not same or not cross:
+            return {"verified": False, "same_GBps": [], "cross_GBps": [], "note": "arena too small to probe"}
+
+        def rate(pair):
+            x, y = (self.buf[o * GIB:o * GIB + nb] for o in pair)
+            two_writes(x, y)
+            best = 0.0
+            for _ in range(reps):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                two_writes(x, y)
+                b.record()
+                b.synchronize()
+                best = max(best, 2 * nb / (a.elapsed_time(b) * 1e-3) / 1e9)
+            return best
+
+        s, c = [rate(p) for p in same], [rate(p) for p in cross]
+        return {"verified": bool(min(c) >= margin * max(s)), "same_GBps": [round(x) for x in s],
+                "cross_GBps": [round(x) for x in c], "pairs_GiB": {"same": same, "cross": cross}}
+
     @staticmethod
     def _midpoint(nbytes: int, traffic) -> int:
         if not traffic:

@@ -414,3 +414,27 @@ def test_gpu_tests_refuse_a_substituted_oracle(tmp_path):
     r = subprocess.run([sys.executable, "-m", "pytest", "tests/test_zz_no_alloc.py", "-m", "gpu", "-q",
                         "-p", "no:cacheprovider"], cwd=ROOT, env=env, capture_output=True, text=True)
     assert r.returncode != 0 and "MA_ORACLE_LIBRARY is set" in r.stdout
+
+
+def test_overlapping_buffers_are_rejected():
+    """Byte ranges that share a byte: MA_ERR_ARG before anything is launched (fake addresses)."""
+    B = 0x100000
+    ok = dict(p=B, m=B + 0x1000, v=B + 0x2000, g=B + 0x3000, lp=B + 0x4000, n=1024)      # 4 KiB apart: disjoint
+    assert _step(**dict(ok, step=0)) == ma.MA_ERR_ARG and b"step" in ma.lib.ma_last_error()  # still the first error
+    for bad in (dict(m=B + 0xFFC), dict(v=B), dict(g=B + 0x2800), dict(lp=B + 0x37FE), dict(p=B + 0x4000 + 2044)):
+        assert _step(**dict(ok, **bad)) == ma.MA_ERR_ARG, bad
+        assert b"overlap" in ma.lib.ma_last_error()
+    # the same through a tensor list: inside one tensor, and between two tensors
+    plan = ma.MultiPlanStruct()
+    prep = ma.lib.ma_multi_prepare
+    inside = (ma.Tensor * 1)(ma.Tensor(B, B + 0x1000, B + 0x2000, B + 0x3000, B + 0x2F00, 1024))
+    assert prep(inside, 1, ma.MA_BF16, ma.MA_BF16, A, 224, None, ctypes.byref(plan)) == ma.MA_ERR_ARG
+    assert b"overlap" in ma.lib.ma_last_error()
+    C = B + 0x10000
+    across = (ma.Tensor * 2)(ma.Tensor(B, B + 0x1000, B + 0x2000, B + 0x3000, B + 0x4000, 1024),
+                             ma.Tensor(C, C + 0x1000, B + 0x1800, C + 0x3000, C + 0x4000, 1024))
+    assert prep(across, 2, ma.MA_BF16, ma.MA_BF16, A, 224, None, ctypes.byref(plan)) == ma.MA_ERR_ARG
+    assert b"tensor 0" in ma.lib.ma_last_error() and b"tensor 1" in ma.lib.ma_last_error()
+    # accumulation
+    assert ma.lib.ma_grad_accumulate(B, B + 2048, ma.MA_BF16, 1024, 1, None) == ma.MA_ERR_ARG
+    assert b"overlap" in ma.lib.ma_last_error()
