@@ -139,8 +139,8 @@ int ma_version(void);
 const char* ma_last_error(void);
 
 /* Bytes of device workspace ma_overflow_norm / ma_multi_overflow_norm need (per-block partial
- * results of the two-level reduction).  Independent of n.  The workspace may be reused by
- * later calls on the same stream; calls on different streams need different workspaces. */
+ * results of the two-level reduction).  Independent of n.  The workspace may be reused by later calls on the same stream; calls on
+ * different streams need different workspaces. */
 size_t ma_workspace_bytes(void);
 
 /* Host helper: the clip coefficient of global-norm clipping,
@@ -230,6 +230,22 @@ int ma_adamw_step_gated(float* p32, float* m, float* v, const void* grad, ma_dty
                         ma_dtype pdt, size_t n, const ma_hyper* hyper, int64_t step,
                         float loss_scale, const ma_norm_result* gate_dev, float max_norm,
                         void* stream);
+
+/* ---- the whole step in one call ---------------------------------------------------------------------- */
+
+/* Scan, gate and update of one flat sub-group (Sec. IV-A: the check validates the gradients, then the
+ * optimizer steps) in one call and TWO launches instead of three: the scan writes its per-block
+ * partial results to ws, and every block of the update launch adds them up itself, in the order
+ * ma_overflow_norm's own second-level launch uses, before it touches any buffer.  *out_dev receives
+ * {overflow, sumsq}, bit-identical to ma_overflow_norm's; p32, m, v, p_lp are updated exactly as by
+ * ma_adamw_step_gated with this max_norm (not at all when overflow is set).  Saves about 5 us per
+ * step, which matters for sub-groups of a few million elements, whose step is launch-bound.
+ * Not for sub-groups that share one global norm (Sec. IV-C): those need all scans, ma_norm_combine,
+ * then the gated updates.  ws as for ma_overflow_norm; it must not overlap any buffer.  n == 0 writes
+ * {0, 0.0}. */
+int ma_optimizer_step(float* p32, float* m, float* v, const void* grad, ma_dtype gdt, void* p_lp,
+                      ma_dtype pdt, size_t n, const ma_hyper* hyper, int64_t step, float loss_scale,
+                      float max_norm, ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream);
 
 /* ---- half-precision optimizer states ---------------------------------------------------------- */
 
@@ -335,6 +351,11 @@ int ma_multi_adamw_step(const ma_multi_plan* plan, const ma_hyper* hyper, int64_
 int ma_multi_adamw_step_gated(const ma_multi_plan* plan, const ma_hyper* hyper, int64_t step,
                               float loss_scale, const ma_norm_result* gate_dev, float max_norm,
                               void* stream);
+
+/* ma_optimizer_step over every tensor of the plan: one scan launch, one update launch. */
+int ma_multi_optimizer_step(const ma_multi_plan* plan, const ma_hyper* hyper, int64_t step, float loss_scale,
+                            float max_norm, ma_norm_result* out_dev, void* ws, size_t ws_bytes,
+                            void* stream);
 
 /* The *_auto forms over a prepared tensor list. */
 int ma_multi_overflow_norm_auto(const ma_multi_plan* plan, const ma_scaler_state* scaler_dev,

@@ -89,6 +89,8 @@ def _load() -> ctypes.CDLL:
         "ma_adamw_step": ([vp, vp, vp, vp, i32, vp, i32, sz, vp, i64, f32, f32, vp], ctypes.c_int),
         "ma_adamw_step_gated": ([vp, vp, vp, vp, i32, vp, i32, sz, vp, i64, f32, vp, f32, vp],
                                 ctypes.c_int),
+        "ma_optimizer_step": ([vp, vp, vp, vp, i32, vp, i32, sz, vp, i64, f32, f32, vp, vp, sz, vp], ctypes.c_int),
+        "ma_multi_optimizer_step": ([vp, vp, i64, f32, f32, vp, vp, sz, vp], ctypes.c_int),
         "ma_multi_table_bytes": ([sz], sz),
         "ma_multi_prepare": ([vp, sz, i32, i32, vp, sz, vp, vp], ctypes.c_int),
         "ma_multi_prepare_bf16": ([vp, sz, i32, vp, sz, vp, vp], ctypes.c_int),
@@ -252,6 +254,21 @@ def adamw_step_gated(p, m, v, grad, p_lp, h: Hyper, step: int, loss_scale: float
                                    loss_scale, _slot(gate, index), max_norm, _stream(stream)))
 
 
+def optimizer_step(p, m, v, grad, p_lp, h: Hyper, step: int, loss_scale: float, max_norm: float,
+                   out: torch.Tensor, ws: torch.Tensor, index: int = 0, stream=None) -> None:
+    """ma_optimizer_step: scan, gate and update of a flat sub-group in one call (two launches)."""
+    _check(lib.ma_optimizer_step(*_step_args(p, m, v, grad, p_lp), ctypes.byref(h), int(step), loss_scale,
+                                 max_norm, _slot(out, index), _dev(ws, "ws"), ws.numel() * ws.element_size(),
+                                 _stream(stream)))
+
+
+def read_result_raw(res: torch.Tensor, index: int = 0):
+    """Synchronising read-back of one ma_norm_result as (overflow: int, sumsq: float)."""
+    raw = res[2 * index:2 * index + 2].cpu().numpy().tobytes()
+    ov, _, ss = struct.unpack("<iid", raw)
+    return ov, ss
+
+
 class MultiPlan:
     """A prepared tensor list (ma_multi_prepare).  Keeps the device table and the tensors alive."""
 
@@ -324,6 +341,14 @@ def multi_adamw_step_gated(plan: MultiPlan, h: Hyper, step: int, loss_scale: flo
                            stream=None) -> None:
     _check(lib.ma_multi_adamw_step_gated(ctypes.byref(plan.plan), ctypes.byref(h), int(step),
                                          loss_scale, _slot(gate, index), max_norm, _stream(stream)))
+
+
+def multi_optimizer_step(plan: MultiPlan, h: Hyper, step: int, loss_scale: float, max_norm: float,
+                         out: torch.Tensor, ws: torch.Tensor, index: int = 0, stream=None) -> None:
+    """ma_multi_optimizer_step: scan, gate and update of a prepared tensor list in one call."""
+    _check(lib.ma_multi_optimizer_step(ctypes.byref(plan.plan), ctypes.byref(h), int(step), loss_scale,
+                                       max_norm, _slot(out, index), _dev(ws, "ws"),
+                                       ws.numel() * ws.element_size(), _stream(stream)))
 
 
 # ---- half-precision optimizer states ---------------------------------------------------------

@@ -478,6 +478,16 @@ __device__ __forceinline__ void step_pipeline(const StepScalars& s, Items& items
 //     same two roundings as the host path (clip coefficient to fp32, then c/S in fp64 to fp32).
 __device__ __forceinline__ bool prepare_step(const StepControl& ctl, StepScalars& s) {
   float loss_scale = ctl.loss_scale;
+  // The scan's per-block partials instead of a finished result: every block adds them up itself, in
+  // the order of the stand-alone finalize kernel (same function, same bits), which saves that launch;
+  // block 0 publishes the result for the caller.
+  NormResult folded;
+  const bool fold = ctl.partials != nullptr;
+  if (fold) {
+    folded = fold_partials(ctl.partials, ctl.partial_count, ctl.inv_scale_sq, nullptr, ctl.threshold,
+                           ctl.packed16);
+    if (blockIdx.x == 0 && threadIdx.x == 0) *ctl.result_out = folded;
+  }
   if (ctl.scaler != nullptr) {
     loss_scale = ctl.scaler->scale;
     double bc1 = 1.0, bc2 = 1.0;
@@ -489,11 +499,13 @@ __device__ __forceinline__ bool prepare_step(const StepControl& ctl, StepScalars
     s.step_size = static_cast<float>(static_cast<double>(ctl.lr) / bc1);
     s.inv_sqrt_bc2 = static_cast<float>(1.0 / __builtin_sqrt(bc2));
   }
-  if (ctl.gate != nullptr) {
-    if (ctl.gate->overflow != 0) return false;
+  if (ctl.gate != nullptr || fold) {
+    const int overflow = fold ? folded.overflow : ctl.gate->overflow;
+    const double sumsq = fold ? folded.sumsq : ctl.gate->sumsq;
+    if (overflow != 0) return false;
     double c = 1.0;
     if (ctl.max_norm > 0.0f) {
-      c = static_cast<double>(ctl.max_norm) / (__builtin_sqrt(ctl.gate->sumsq) + 1e-6);
+      c = static_cast<double>(ctl.max_norm) / (__builtin_sqrt(sumsq) + 1e-6);
       c = (c < 1.0) ? c : 1.0;
     }
     const float cf = static_cast<float>(c);

@@ -45,6 +45,7 @@ int fail_hip(hipError_t e, const char* what) {
 
 constexpr uint32_t kPlanMagic = 0x4D415450u;  // "MATP"
 
+
 bool dtype_ok(int dt) { return dt == MA_F32 || dt == MA_BF16 || dt == MA_F16; }
 size_t elem_bytes(int dt) { return dt == MA_F32 ? 4 : 2; }
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -231,6 +232,10 @@ struct StepRequest {
   const void* scaler = nullptr;          // device ma_scaler_state (auto variants)
   float max_norm = 0.0f;
   bool gated = false, automatic = false;
+  // whole-step calls: the update launch adds up the scan's partials itself and publishes the result
+  const void* partials = nullptr;
+  uint32_t partial_count = 0;
+  ma_norm_result* result_out = nullptr;
 };
 
 int check_request(const StepRequest& q) {
@@ -241,7 +246,9 @@ int check_request(const StepRequest& q) {
     if (!q.scaler) return fail(MA_ERR_NULL, "scaler_dev is NULL");
     if (!aligned(q.scaler, 8)) return fail(MA_ERR_ALIGN, "scaler_dev must be 8-byte aligned");
   }
-  if (q.gated || q.automatic) {
+  if (q.result_out) {
+    if (std::isnan(q.max_norm)) return fail(MA_ERR_ARG, "max_norm is NaN");
+  } else if (q.gated || q.automatic) {
     if (!q.gate) return fail(MA_ERR_NULL, "gate_dev is NULL");
     if (!aligned(q.gate, 8)) return fail(MA_ERR_ALIGN, "gate_dev must be 8-byte aligned");
     if (std::isnan(q.max_norm)) return fail(MA_ERR_ARG, "max_norm is NaN");
@@ -263,7 +270,7 @@ int step_common(const ma::Desc* row, const ma_multi_plan* plan, uint64_t chunks,
                 int pdt, const StepRequest& q, void* stream) {
   int cus = 0;
   if (int rc = device_cus(&cus)) return rc;
-  const bool host_gscale = !(q.gated || q.automatic);
+  const bool host_gscale = !(q.gated || q.automatic || q.result_out);
   const ma::StepScalars s = host_scalars(*q.hyper, q.automatic ? 1 : q.step,
                                          q.automatic ? 1.0f : q.loss_scale,
                                          host_gscale ? q.clip_coef : 1.0f);
@@ -274,6 +281,14 @@ int step_common(const ma::Desc* row, const ma_multi_plan* plan, uint64_t chunks,
   ctl.loss_scale = q.loss_scale;
   ctl.lr = q.hyper->lr;
   ctl.bias_correction = q.hyper->bias_correction;
+  if (q.result_out) {
+    ctl.partials = static_cast<const ma::NormPartial*>(q.partials);
+    ctl.partial_count = q.partial_count;
+    ctl.result_out = reinterpret_cast<ma::NormResult*>(q.result_out);
+    ctl.inv_scale_sq = 1.0 / (double(q.loss_scale) * double(q.loss_scale));
+    ctl.threshold = ma::norm_threshold(gdt);
+    ctl.packed16 = gdt != MA_F32;
+  }
   hipError_t e = ma::launch_step(row, plan ? plan_rows(plan) : nullptr,
                                  plan ? uint32_t(plan->entries) : 1u, chunks, sdt, gdt, pdt, s, ctl,
                                  plan ? plan_queue(plan) : nullptr, cus, static_cast<hipStream_t>(stream));
@@ -281,31 +296,40 @@ int step_common(const ma::Desc* row, const ma_multi_plan* plan, uint64_t chunks,
   return MA_OK;
 }
 
+// Every check of a flat update call; fills the row and its number of work items (0 for n == 0).
 // sdt: MA_F32 (fp32 master states, optional 16-bit copy) or MA_BF16 (states held in bf16).
-int flat_step(void* p, void* m, void* v, const void* grad, ma_dtype gdt, void* p_lp, ma_dtype pdt,
-              int sdt, size_t n, const StepRequest& q, void* stream) {
+int flat_step_check(void* p, void* m, void* v, const void* grad, ma_dtype gdt, void* p_lp, ma_dtype pdt,
+                    int sdt, size_t n, const StepRequest& q, ma::Desc& d, uint64_t& sc) {
+  sc = 0;
   if (int rc = check_request(q)) return rc;
   if (!dtype_ok(gdt)) return fail(MA_ERR_DTYPE, "unsupported gradient dtype %d", int(gdt));
   if (p_lp && !(pdt == MA_BF16 || pdt == MA_F16))
     return fail(MA_ERR_DTYPE, "low-precision parameter dtype must be MA_BF16 or MA_F16");
   if (n == 0) return MA_OK;
   if (!p || !m || !v || !grad) return fail(MA_ERR_NULL, "p, m, v and grad must not be NULL");
-  ma::Desc d{};
+  d = ma::Desc{};
   d.p = static_cast<float*>(p);
   d.m = static_cast<float*>(m);
   d.v = static_cast<float*>(v);
   d.g = grad;
   d.lp = p_lp;
   d.n = n;
-  uint64_t nc = 0, sc = 0;
+  uint64_t nc = 0;
   if (int rc = plan_row(d, gdt, p_lp != nullptr, &nc, &sc, sdt == MA_F32 ? 4 : 2)) return rc;
-  {
-    std::vector<Range> r;
-    row_ranges(d, gdt, sdt == MA_F32 ? 4 : 2, 0, r);
-    const Range *a = nullptr, *b = nullptr;
-    if (any_overlap(r, &a, &b))
-      return fail(MA_ERR_ARG, "buffers overlap: [%p, %p) and [%p, %p)", (void*)a->lo, (void*)a->hi, (void*)b->lo, (void*)b->hi);
-  }
+  std::vector<Range> r;
+  row_ranges(d, gdt, sdt == MA_F32 ? 4 : 2, 0, r);
+  const Range *a = nullptr, *b = nullptr;
+  if (any_overlap(r, &a, &b))
+    return fail(MA_ERR_ARG, "buffers overlap: [%p, %p) and [%p, %p)", (void*)a->lo, (void*)a->hi, (void*)b->lo, (void*)b->hi);
+  return MA_OK;
+}
+
+int flat_step(void* p, void* m, void* v, const void* grad, ma_dtype gdt, void* p_lp, ma_dtype pdt,
+              int sdt, size_t n, const StepRequest& q, void* stream) {
+  ma::Desc d{};
+  uint64_t sc = 0;
+  if (int rc = flat_step_check(p, m, v, grad, gdt, p_lp, pdt, sdt, n, q, d, sc)) return rc;
+  if (n == 0) return MA_OK;
   return step_common(&d, nullptr, sc, sdt, gdt, p_lp ? int(pdt) : ma::kNoLp, q, stream);
 }
 
@@ -321,7 +345,7 @@ void* const kLibraryScratch = reinterpret_cast<void*>(uintptr_t(1));
 
 int norm_common(const ma::Desc* row, const ma_multi_plan* plan, uint64_t chunks, int gdt,
                 float loss_scale, const void* scaler, ma_norm_result* out_dev, void* ws,
-                size_t ws_bytes, void* stream) {
+                size_t ws_bytes, void* stream, uint32_t* grid_out = nullptr) {
   if (scaler) {
     if (!aligned(scaler, 8)) return fail(MA_ERR_ALIGN, "scaler_dev must be 8-byte aligned");
   } else if (int rc = check_scale(loss_scale)) {
@@ -343,13 +367,14 @@ int norm_common(const ma::Desc* row, const ma_multi_plan* plan, uint64_t chunks,
                                  static_cast<const ma::ScalerState*>(scaler),
                                  static_cast<ma::NormPartial*>(ws),
                                  reinterpret_cast<ma::NormResult*>(out_dev), cus,
-                                 static_cast<hipStream_t>(stream));
+                                 static_cast<hipStream_t>(stream), grid_out);
   if (e != hipSuccess) return fail_hip(e, "scan kernel launch");
   return MA_OK;
 }
 
 int flat_norm(const void* grad, ma_dtype gdt, size_t n, float loss_scale, const void* scaler,
-              bool automatic, ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream) {
+              bool automatic, ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream,
+              uint32_t* grid_out = nullptr) {
   if (!dtype_ok(gdt)) return fail(MA_ERR_DTYPE, "unsupported gradient dtype %d", int(gdt));
   if (automatic && !scaler) return fail(MA_ERR_NULL, "scaler_dev is NULL");
   if (n > 0 && !grad) return fail(MA_ERR_NULL, "grad is NULL");
@@ -360,7 +385,7 @@ int flat_norm(const void* grad, ma_dtype gdt, size_t n, float loss_scale, const 
   if (n > 0) {
     if (int rc = plan_row(d, gdt, false, &chunks, nullptr)) return rc;
   }
-  return norm_common(&d, nullptr, chunks, gdt, loss_scale, scaler, out_dev, ws, ws_bytes, stream);
+  return norm_common(&d, nullptr, chunks, gdt, loss_scale, scaler, out_dev, ws, ws_bytes, stream, grid_out);
 }
 
 // Shared by the two prepare calls: `row(i, d)` fills the pointers and n of tensor i and returns
@@ -564,6 +589,62 @@ int ma_adamw_step_gated(float* p32, float* m, float* v, const void* grad, ma_dty
   q.max_norm = max_norm;
   q.gated = true;
   return flat_step(p32, m, v, grad, gdt, p_lp, pdt, MA_F32, n, q, stream);
+}
+
+int ma_optimizer_step(float* p32, float* m, float* v, const void* grad, ma_dtype gdt, void* p_lp,
+                      ma_dtype pdt, size_t n, const ma_hyper* hyper, int64_t step, float loss_scale,
+                      float max_norm, ma_norm_result* out_dev, void* ws, size_t ws_bytes, void* stream) {
+  StepRequest q;
+  q.hyper = hyper;
+  q.step = step;
+  q.loss_scale = loss_scale;
+  q.max_norm = max_norm;
+  q.result_out = out_dev;
+  q.partials = ws;
+  // every argument of both launches is checked before the first one is enqueued
+  if (!out_dev) return fail(MA_ERR_NULL, "out_dev is NULL");
+  if (!aligned(out_dev, 8)) return fail(MA_ERR_ALIGN, "out_dev must be 8-byte aligned");
+  if (int rc = check_ws(ws, ws_bytes)) return rc;
+  ma::Desc d{};
+  uint64_t sc = 0;
+  if (int rc = flat_step_check(p32, m, v, grad, gdt, p_lp, pdt, MA_F32, n, q, d, sc)) return rc;
+  if (n == 0)  // nothing to update: the plain scan writes {0, 0.0}
+    return flat_norm(grad, gdt, 0, loss_scale, nullptr, false, out_dev, ws, ws_bytes, stream);
+  {
+    std::vector<Range> r;
+    row_ranges(d, gdt, 4, 0, r);
+    r.push_back(range_of(ws, ma_workspace_bytes()));
+    r.push_back(range_of(out_dev, sizeof(ma_norm_result)));
+    const Range *a = nullptr, *b = nullptr;
+    if (any_overlap(r, &a, &b))
+      return fail(MA_ERR_ARG, "buffers overlap: [%p, %p) and [%p, %p)", (void*)a->lo, (void*)a->hi, (void*)b->lo, (void*)b->hi);
+  }
+  if (int rc = flat_norm(grad, gdt, n, loss_scale, nullptr, false, out_dev, ws, ws_bytes, stream, &q.partial_count))
+    return rc;
+  return step_common(&d, nullptr, sc, MA_F32, gdt, p_lp ? int(pdt) : ma::kNoLp, q, stream);
+}
+
+int ma_multi_optimizer_step(const ma_multi_plan* plan, const ma_hyper* hyper, int64_t step, float loss_scale,
+                            float max_norm, ma_norm_result* out_dev, void* ws, size_t ws_bytes,
+                            void* stream) {
+  StepRequest q;
+  q.hyper = hyper;
+  q.step = step;
+  q.loss_scale = loss_scale;
+  q.max_norm = max_norm;
+  q.result_out = out_dev;
+  q.partials = ws;
+  if (int rc = check_plan(plan)) return rc;
+  if (!out_dev) return fail(MA_ERR_NULL, "out_dev is NULL");
+  if (!aligned(out_dev, 8)) return fail(MA_ERR_ALIGN, "out_dev must be 8-byte aligned");
+  if (int rc = check_ws(ws, ws_bytes)) return rc;
+  if (int rc = check_request(q)) return rc;
+  if (plan->entries == 0)
+    return norm_common(nullptr, plan, plan->norm_chunks, plan->gdt, loss_scale, nullptr, out_dev, ws, ws_bytes, stream);
+  if (int rc = norm_common(nullptr, plan, plan->norm_chunks, plan->gdt, loss_scale, nullptr, out_dev, ws,
+                           ws_bytes, stream, &q.partial_count))
+    return rc;
+  return step_common(nullptr, plan, plan->step_chunks, int(plan->sdt), plan->gdt, plan->pdt, q, stream);
 }
 
 int ma_adamw_step_auto(float* p32, float* m, float* v, const void* grad, ma_dtype gdt, void* p_lp,

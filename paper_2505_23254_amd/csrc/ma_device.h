@@ -152,6 +152,13 @@ struct StepControl {
   float loss_scale;
   float lr;
   int32_t bias_correction;
+  // whole-step calls: the scan's per-block partials take the place of `gate`
+  const NormPartial* partials;  // null: not a whole-step call
+  NormResult* result_out;       // where block 0 publishes the folded scan result
+  double inv_scale_sq;
+  uint32_t partial_count;
+  uint32_t threshold;  // sign-stripped pattern of infinity in the gradient's format
+  int32_t packed16;    // partial maxima hold two 16-bit lanes
 };
 
 // ---- beta^t for the bias corrections -----------------------------------------------------------
@@ -410,6 +417,55 @@ __device__ __forceinline__ void norm_block_finish(NormAcc<GDT>& acc, NormPartial
     out.pad = 0;
     partials[blockIdx.x] = out;
   }
+}
+
+// Second level of the scan: the whole block adds `count` per-block partials.  Thread t takes partials
+// t, t + 256, ... in increasing order, then the same wave / LDS fold as above; the order is a function
+// of `count` alone, so whoever calls this (the finalize kernel, or every block of an update launch)
+// gets the same bits.  Every thread of the block must call it; every thread receives the result.
+__device__ __forceinline__ NormResult fold_partials(const NormPartial* __restrict__ partials, uint32_t count,
+                                                    double inv_scale_sq, const ScalerState* scaler,
+                                                    uint32_t threshold, int packed16) {
+  __shared__ double f_sum[kBlock / kWave];
+  __shared__ uint32_t f_max[kBlock / kWave];
+  __shared__ NormResult f_result;
+  double t = 0.0;
+  uint32_t mx = 0;
+  for (uint32_t i = threadIdx.x; i < count; i += kBlock) {
+    t += partials[i].sum;
+    const uint32_t w = partials[i].maxabs;
+    // fold the two 16-bit lanes into one value; fp32 patterns pass through
+    const uint32_t f = packed16 ? ((w & 0xFFFFu) > (w >> 16) ? (w & 0xFFFFu) : (w >> 16)) : w;
+    mx = f > mx ? f : mx;
+  }
+  t = wave_sum(t);
+  mx = wave_max_pattern<false>(mx);
+  const int wave = threadIdx.x / kWave;
+  if ((threadIdx.x & (kWave - 1)) == 0) {
+    f_sum[wave] = t;
+    f_max[wave] = mx;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double tot = f_sum[0];
+    uint32_t m = f_max[0];
+#pragma unroll
+    for (int k = 1; k < kBlock / kWave; ++k) {
+      tot += f_sum[k];
+      m = f_max[k] > m ? f_max[k] : m;
+    }
+    NormResult r;
+    r.overflow = (m >= threshold) ? 1 : 0;
+    r.reserved = 0;
+    if (scaler != nullptr) {
+      const double sc = static_cast<double>(scaler->scale);
+      inv_scale_sq = 1.0 / (sc * sc);
+    }
+    r.sumsq = tot * inv_scale_sq;
+    f_result = r;
+  }
+  __syncthreads();
+  return f_result;
 }
 
 }  // namespace ma

@@ -23,9 +23,14 @@ constexpr uint32_t kMaxNormBlocks = 8192;
 // Exactly one of row_host (flat sub-group, row passed by value) and table_dev (tensor list) is
 // non-null.  `chunks` is the number of work items over all rows.  With a scaler state the
 // finalize kernel takes the loss scale from device memory instead of inv_scale_sq.
+// grid_out != null: no finalize launch; *grid_out receives the number of partials written, for a
+// following launch that adds them up itself (StepControl::partials).
 hipError_t launch_norm(const Desc* row_host, const Desc* table_dev, uint32_t rows, uint64_t chunks,
                        int gdt, double inv_scale_sq, const ScalerState* scaler, NormPartial* partials,
-                       NormResult* out, int device_cus, hipStream_t stream);
+                       NormResult* out, int device_cus, hipStream_t stream, uint32_t* grid_out = nullptr);
+
+// Sign-stripped bit pattern of infinity in the gradient format (the scan's overflow threshold).
+uint32_t norm_threshold(int gdt);
 
 // Second level of the scan: one block adds `count` per-block partials in index order.
 hipError_t launch_norm_finalize(const NormPartial* partials, uint32_t count, int gdt, double inv_scale_sq,

@@ -124,51 +124,15 @@ __global__ __launch_bounds__(kBlock) void norm_multi_kernel(const Desc* __restri
   norm_block_finish<GDT>(acc, partials);
 }
 
-// Second level: one block adds `count` partials.  Thread t takes partials t, t+256, ... in
-// increasing order, then the same wave/LDS fold as above; the order is a function of `count`
-// alone.  `threshold` is the sign-stripped pattern of infinity for the gradient format.
+// Second level as a launch of its own: one block adds the partials (fold_partials) and writes the result.
+// `threshold` is the sign-stripped pattern of infinity for the gradient format.
 __global__ __launch_bounds__(kBlock) void norm_finalize_kernel(const NormPartial* __restrict__ partials,
                                                               uint32_t count, double inv_scale_sq,
                                                               const ScalerState* scaler,
                                                               uint32_t threshold, int packed16,
                                                               NormResult* out) {
-  __shared__ double s_sum[kBlock / kWave];
-  __shared__ uint32_t s_max[kBlock / kWave];
-  double t = 0.0;
-  uint32_t mx = 0;
-  for (uint32_t i = threadIdx.x; i < count; i += kBlock) {
-    t += partials[i].sum;
-    const uint32_t w = partials[i].maxabs;
-    // fold the two 16-bit lanes into one value; fp32 patterns pass through
-    const uint32_t f = packed16 ? ((w & 0xFFFFu) > (w >> 16) ? (w & 0xFFFFu) : (w >> 16)) : w;
-    mx = f > mx ? f : mx;
-  }
-  t = wave_sum(t);
-  mx = wave_max_pattern<false>(mx);
-  const int wave = threadIdx.x / kWave;
-  if ((threadIdx.x & (kWave - 1)) == 0) {
-    s_sum[wave] = t;
-    s_max[wave] = mx;
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    double tot = s_sum[0];
-    uint32_t m = s_max[0];
-#pragma unroll
-    for (int k = 1; k < kBlock / kWave; ++k) {
-      tot += s_sum[k];
-      m = s_max[k] > m ? s_max[k] : m;
-    }
-    NormResult r;
-    r.overflow = (m >= threshold) ? 1 : 0;
-    r.reserved = 0;
-    if (scaler != nullptr) {
-      const double sc = static_cast<double>(scaler->scale);
-      inv_scale_sq = 1.0 / (sc * sc);
-    }
-    r.sumsq = tot * inv_scale_sq;
-    *out = r;
-  }
+  const NormResult r = fold_partials(partials, count, inv_scale_sq, scaler, threshold, packed16);
+  if (threadIdx.x == 0) *out = r;
 }
 
 // Adds scan results of several sub-groups in index order (single thread: count is tiny).
@@ -194,9 +158,11 @@ static uint32_t threshold_of(int gdt) {
   return gdt == kBF16 ? 0x7F80u : gdt == kF16 ? 0x7C00u : 0x7F800000u;
 }
 
+uint32_t norm_threshold(int gdt) { return threshold_of(gdt); }
+
 hipError_t launch_norm(const Desc* row_host, const Desc* table_dev, uint32_t rows, uint64_t chunks,
                        int gdt, double inv_scale_sq, const ScalerState* scaler, NormPartial* partials,
-                       NormResult* out, int device_cus, hipStream_t stream) {
+                       NormResult* out, int device_cus, hipStream_t stream, uint32_t* grid_out) {
   uint64_t want = uint64_t(device_cus) * MA_NORM_BLOCKS_PER_CU;
   if (want > kMaxNormBlocks) want = kMaxNormBlocks;
   const uint32_t grid = static_cast<uint32_t>(chunks < want ? (chunks ? chunks : 1) : want);
@@ -219,6 +185,10 @@ hipError_t launch_norm(const Desc* row_host, const Desc* table_dev, uint32_t row
   }
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
+  if (grid_out != nullptr) {  // the caller's next launch adds up the partials itself
+    *grid_out = grid;
+    return hipSuccess;
+  }
   return launch_norm_finalize(partials, grid, gdt, inv_scale_sq, scaler, out, stream);
 }
 
