@@ -12,6 +12,10 @@
 // overwrite + scan 8.96 / 8.20 / 7.50 / 7.58 ms with 6 / 8 / 12 / 16 groups against 7.46 ms for the
 // plain overwrite; add + scan 12.93 / 12.64 / 12.555 / 12.76 ms with 4 / 6 / 8 / 10 against 12.55).
 //
+// The memory-side cache does not help here as it helps the update after a scan: writing the buffer
+// without the non-temporal hint, with or without also loading the old contents that way, leaves
+// the update kernel that reads it next where it was (n = 5e7: 0.233-0.240 ms either way).
+//
 // The SCAN variant also runs the overflow check of Sec. IV-D / Algorithm 1 (with its fp32 mask)
 // and the sum of squares over the values it has just written: after the last micro-batch of an
 // iteration (Sec. IV-A: the check validates the accumulated gradients before the optimizer step)

@@ -40,7 +40,7 @@ constexpr int kNoLp = 3;  // update kernel variant that writes no low-precision 
 #define MA_NORM_KEEP_MIB 320  // gradient bytes (MiB) the scan leaves in the memory-side cache for the update kernel
 #endif
 #ifndef MA_STEP_UNROLL_BF16
-#define MA_STEP_UNROLL_BF16 6  // 8-element groups per lane and tile when p, m, v are held in bf16
+#define MA_STEP_UNROLL_BF16 8  // 8-element groups per lane and tile when p, m, v are held in bf16
 #endif
 #ifndef MA_STEP_PACE_MULTI
 #define MA_STEP_PACE_MULTI 32  // s_sleep units (64 clocks each) before a tile's stores: multi-tensor kernel, fp32 states

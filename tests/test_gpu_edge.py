@@ -93,7 +93,7 @@ def test_list_step_in_the_subnormal_range_is_bit_exact(case):
 
 def test_bf16_state_step_in_the_subnormal_range_is_bit_exact():
     """States held in bf16 and stored by truncation, with subnormal patterns in p, m, v and g."""
-    n = 40_001
+    n = 70_001                                             # several 16,384-element work items and a ragged tail
     p, m, v, g, gdt, scale, clip, eps = synth.extreme_case("subnormal", n, seed=2)
     bp, bm, bv = ((x.view(np.uint32) >> 16).astype(np.uint16) for x in (p, m, v))      # inputs: upper halves
     h_ref, h = oracle.hyper(1e-3, 0.9, 0.999, eps, 0.1, 1), ma.hyper(1e-3, 0.9, 0.999, eps, 0.1, 1)

@@ -555,11 +555,11 @@ def test_list_with_late_items_drawn_on_demand_eager_and_graph():
 
 
 def test_bf16_state_list_with_late_items_drawn_on_demand():
-    """The same size class for a list whose p, m, v are held in bf16 (1/8-scale 8B shapes, 1.0e9
-    elements, work items of 12,288 elements): two iterations on one plan, every truncated pattern of
+    """The same size class for a list whose p, m, v are held in bf16 (1/6-scale 8B shapes, 1.34e9
+    elements, work items of 16,384 elements): two iterations on one plan, every truncated pattern of
     every tensor against the oracle, counters back at zero."""
-    _need_gib(24)
-    shapes = synth.scaled_shapes(synth.llama3_8b_shapes(), 8, ragged=True)
+    _need_gib(32)
+    shapes = synth.scaled_shapes(synth.llama3_8b_shapes(), 6, ragged=True)
     cfg = synth.FlatConfig("t", 0, seed=97, m_std=1e-3, v_std=1e-6, lr=1e-2, weight_decay=0.1, eps=1e-6,
                            max_norm=1.0)
     ls = synth.make_list(shapes, cfg, device="cuda", align_elems=1)

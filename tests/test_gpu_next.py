@@ -120,8 +120,9 @@ def _bf16_state(cfg, n):
     return st, p, m, v
 
 
-BF_SIZES = [0, 1, 3, 4, 5, 7, 8, 9, 15, 16, 17, 1023, 1024, 4096, 4097, 8191, 8192, 8193, 12287, 12288, 12289, 16385,
-            24577, 100_003, (1 << 20) + 5]
+# a work item of this variant is 16,384 elements (256 lanes x 8 groups x 8 elements)
+BF_SIZES = [0, 1, 3, 4, 5, 7, 8, 9, 15, 16, 17, 1023, 1024, 4096, 4097, 8191, 8192, 8193, 12287, 12288, 12289, 16383,
+            16384, 16385, 24577, 32767, 32768, 32769, 49153, 100_003, (1 << 20) + 5]
 
 
 @pytest.mark.parametrize("gdt,scale,clip", [("bf16", 1.0, 1.0), ("bf16", 1.0, 0.3), ("f16", 1024.0, 0.5),
