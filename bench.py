@@ -48,20 +48,24 @@ SCAN_BYTES_PER_PARAM = 2.0     # scan kernel: read g
 # kernels are built from differs, the figure is reported as null.
 STEP_SOURCES = ("ma_device.h", "ma_internal.h", "ma_norm.hip", "ma_adamw.hip")
 ACCUM_SOURCES = ("ma_device.h", "ma_internal.h", "ma_norm.hip", "ma_accum.hip")
-STEP_SHA256 = "e6581c7bde40ca11d98daf2248a3d9872d64f63190af7998662f21e0310abe97"
-ACCUM_SHA256 = "c78d1b8e49ea08329a9d4f68966fce04916c396c5fb808a68931f25c21266824"
+STEP_SHA256 = "250b097cc6faf43480ba435598fa58e3c2a693698f5cec00ffca131c49ea7d3c"
+ACCUM_SHA256 = "310a98ba66618c755c626d4298316e786679b0d6f5cf32889dcb49d7964e49d0"
 MEASURED_TRAFFIC = {      # workload: (bytes per launch, sources, their digest when measured)
-    "llama3_8b": (224846990735, STEP_SOURCES, STEP_SHA256),
-    "fp32grad_8b": (240908548336, STEP_SOURCES, STEP_SHA256),
-    "auto_fp16_8b": (224846981559, STEP_SOURCES, STEP_SHA256),
-    "qwen14b_4sub": (87973119559, STEP_SOURCES, STEP_SHA256),
-    "bf16_states_8b": (112423220365, STEP_SOURCES, STEP_SHA256),
-    "accumulate_8b": (80301725552, ACCUM_SOURCES, ACCUM_SHA256),
+    "llama3_8b": (224847235573, STEP_SOURCES, STEP_SHA256),
+    "flat_1e8": (2800296479, STEP_SOURCES, STEP_SHA256),
+    "fp16_5e7": (1400284392, STEP_SOURCES, STEP_SHA256),
+    "fp32grad_8b": (240908651118, STEP_SOURCES, STEP_SHA256),
+    "auto_fp16_8b": (224847203550, STEP_SOURCES, STEP_SHA256),
+    "qwen14b_4sub": (87973268477, STEP_SOURCES, STEP_SHA256),
+    "bf16_states_8b": (112423817570, STEP_SOURCES, STEP_SHA256),
+    "accumulate_8b": (80301732827, ACCUM_SOURCES, ACCUM_SHA256),
 }
 
 
 TRAFFIC_SOURCE = {
-    "llama3_8b": "profiles/hbm_traffic_counters__llama3_8b.txt",
+    "llama3_8b": "profiles/step_and_norm_multi_kernels__llama3_8b.txt",
+    "flat_1e8": "profiles/step_and_norm_flat_kernels__flat_1e8.txt",
+    "fp16_5e7": "profiles/step_and_norm_flat_kernels__fp16_5e7.txt",
     "fp32grad_8b": "profiles/step_and_norm_multi_kernels__fp32grad_8b.txt",
     "auto_fp16_8b": "profiles/step_and_norm_multi_kernels__auto_fp16_8b.txt",
     "qwen14b_4sub": "profiles/step_and_norm_flat_kernels__qwen14b_4sub.txt",
