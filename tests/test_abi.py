@@ -438,3 +438,15 @@ def test_overlapping_buffers_are_rejected():
     # accumulation
     assert ma.lib.ma_grad_accumulate(B, B + 2048, ma.MA_BF16, 1024, 1, None) == ma.MA_ERR_ARG
     assert b"overlap" in ma.lib.ma_last_error()
+
+
+def test_probe_argument_errors():
+    f, g = ma.lib.ma_probe_update_mix, ma.lib.ma_probe_two_writes
+    assert f(A, A, A, A, A, 1 << 20, 3, None) == ma.MA_ERR_ARG
+    assert f(A, A, None, A, A, 1 << 20, 4, None) == ma.MA_ERR_NULL
+    assert f(A, A, A, A, None, 1 << 20, 4, None) == ma.MA_ERR_NULL          # the 16-bit output is needed with 4-byte states
+    assert f(A, A + 4, A, A, A, 1 << 20, 4, None) == ma.MA_ERR_ALIGN
+    assert f(A, A, A, A, A, 100, 4, None) == ma.MA_ERR_ARG
+    assert g(A, None, 1 << 20, None) == ma.MA_ERR_NULL
+    assert g(A, A + 8, 1 << 20, None) == ma.MA_ERR_ALIGN
+    assert g(A, A, 1024, None) == ma.MA_ERR_ARG
