@@ -100,9 +100,9 @@ class Workload:
 
     def __init__(self, name, ma, layout="streams", arena=None, rotate=1):
         # arena: an hbm.DeviceArena (placement "region": the state is cut from one whole-device
-        # allocation at the offset that splits its traffic evenly over two of the three 96 GiB HBM
-        # regions), or None (placement "plain": a fresh allocation of just the state's size, wherever
-        # the driver puts it)
+        # allocation: p | m | v | g at the offset that splits their traffic evenly over two of the three
+        # 96 GiB HBM regions, the write-only parameter copy in the third), or None (placement "plain":
+        # a fresh allocation of just the state's size, wherever the driver puts it)
         self.name, self.ma, self.layout = name, ma, "flat"
         self.placement = "region" if arena is not None else "plain"
         self.device_arena = arena
@@ -112,6 +112,19 @@ class Workload:
             try:
                 return self.device_arena.window(nbytes, traffic)
             except ValueError as e:        # the arena is smaller than the state
+                log("bench.py: %s; falling back to a plain allocation" % e)
+                self.device_arena = None
+                self.placement = "plain"
+                torch.cuda.empty_cache()
+                return None
+
+        def place_state(parts, traffic):
+            """p | m | v | g and p_lp as two views (see hbm.DeviceArena.split_window)."""
+            if self.device_arena is None:
+                return None
+            try:
+                return self.device_arena.split_window(parts[0], traffic[:4], parts[1])
+            except ValueError as e:
                 log("bench.py: %s; falling back to a plain allocation" % e)
                 self.device_arena = None
                 self.placement = "plain"
@@ -132,9 +145,10 @@ class Workload:
             self.cfg = cfg
             self.layout = layout
             shapes = synth.llama3_8b_shapes()
-            self.state = synth.make_list(shapes, cfg, device="cuda", layout=layout,
-                                         arena=place(synth.list_state_bytes(shapes, layout, gdt=cfg.gdt),
-                                                     synth.list_traffic(shapes, layout, gdt=cfg.gdt)))
+            where = (place_state(synth.list_state_parts(shapes, gdt=cfg.gdt), synth.list_traffic(shapes, gdt=cfg.gdt))
+                     if layout == "streams" else
+                     place(synth.list_state_bytes(shapes, layout, gdt=cfg.gdt), None))
+            self.state = synth.make_list(shapes, cfg, device="cuda", layout=layout, arena=where)
             self.plan = ma.MultiPlan(self.state.p, self.state.m, self.state.v, self.state.g,
                                      self.state.p_lp)
             self.n = self.plan.total
@@ -147,7 +161,7 @@ class Workload:
             self.cfg = cfg
             total = sum(n for _, n in synth.qwen14b_class_shapes())
             self.flat = synth.make_flat(cfg, device="cuda", n=total,
-                                        arena=place(synth.flat_state_bytes(total), synth.flat_traffic(total)))
+                                        arena=place_state(synth.flat_state_parts(total), synth.flat_traffic(total)))
             self.n = total
             self.kind = "sub"
             self.parts = ma.new_result(4)
@@ -194,9 +208,9 @@ class Workload:
             self.cfg = cfg
             self.layout = layout
             shapes = synth.llama3_8b_shapes()
-            self.state = synth.make_list(shapes, cfg, device="cuda", layout=layout,
-                                         arena=place(synth.list_state_bytes(shapes, layout),
-                                                     synth.list_traffic(shapes, layout)))
+            where = (place_state(synth.list_state_parts(shapes), synth.list_traffic(shapes))
+                     if layout == "streams" else place(synth.list_state_bytes(shapes, layout), None))
+            self.state = synth.make_list(shapes, cfg, device="cuda", layout=layout, arena=where)
             self.plan = ma.MultiPlan(self.state.p, self.state.m, self.state.v, self.state.g,
                                      self.state.p_lp)
             self.n = self.plan.total
@@ -211,7 +225,8 @@ class Workload:
             cfg = synth.config({"flat_1e8": "c2", "fp16_5e7": "c3a", "c1": "c1", "c1_onecall": "c1"}[name])
             self.cfg = cfg
             self.flat = synth.make_flat(cfg, device="cuda",
-                                        arena=place(synth.flat_state_bytes(cfg.n), synth.flat_traffic(cfg.n)))
+                                        arena=place_state(synth.flat_state_parts(cfg.n, cfg.gdt),
+                                                          synth.flat_traffic(cfg.n, cfg.gdt)))
             # --rotate K: K distinct sub-groups of this shape, one per step in turn, so that a small
             # sub-group is measured from HBM and not from the caches (256 MB of Infinity Cache)
             self.flats = [self.flat]
@@ -513,9 +528,11 @@ def main():
         nb = args.copy_calibration
         if wl.device_arena is not None:      # the arena holds the device's memory: use its unused tail
             buf = wl.device_arena.buf
-            state = (wl.state.arena if wl.kind in ("multi", "auto") else
-                     wl.raw if wl.kind in ("bf16", "accum") else wl.flat.arena)
-            tail = buf.numel() - (state.data_ptr() - buf.data_ptr() + state.numel())
+            fl = wl.state.flat if wl.kind in ("multi", "auto") else getattr(wl, "flat", None)
+            used = [wl.raw] if wl.kind in ("bf16", "accum") else \
+                [wl.state.arena] if fl is None else [fl.p, fl.m, fl.v, fl.g, fl.p_lp]
+            end = max(t.data_ptr() + t.numel() * t.element_size() for t in used) - buf.data_ptr()
+            tail = buf.numel() - end
             if tail < 2 * nb:
                 sys.exit("bench.py: --copy-calibration needs %d free bytes behind the state" % (2 * nb))
             src, dst = buf[-2 * nb:-nb], buf[-nb:]

@@ -7,10 +7,16 @@ Measured on MI355X (two-stream write and mixed read/write probes over a whole-de
   read/write mix of the update kernel: ~5.3 TB/s inside one region);
 * one allocation that takes (nearly) all free device memory maps linearly onto the regions: byte
   offset x of the allocation lies in region x // 96 GiB;
-* the update kernel is fastest when its traffic splits evenly over two regions (measured on the
-  8B-shaped state: 6.4 TB/s with the state straddling a region boundary half and half, 5.85-6.0
-  TB/s with 80 % of it inside one region; three-way splits were not better than the even two-way
-  split).
+* the update kernel is fastest when the traffic of the buffers it updates in place (p, m, v, read
+  and written) splits evenly over two regions (measured on the 8B-shaped state: 6.4 TB/s with the
+  state straddling a region boundary half and half, 5.85-6.0 TB/s with 80 % of it inside one region;
+  three-way splits of p, m, v were not better than the even two-way split);
+* a WRITE-ONLY stream (the 16-bit parameter copy) is best kept out of those two regions: with the copy
+  in the third region the same kernel reaches 6.47 TB/s (34.75 instead of 35.15 ms on the 8B-shaped
+  list; insensitive to shifts of +-4 GiB, to where in the third region the copy lies, and to whether
+  the gradient lies before p or behind v).  A read-only stream there makes things worse (gradient in
+  the third region: 6.26-6.35 TB/s).  A probe with separate output buffers says the same: what the
+  memory system rewards is write traffic spread over more regions than the reads.
 
 Hence this helper: take the device's free memory as one arena and hand out, for a state of a given
 size, the window of the arena whose traffic midpoint sits on a region boundary.  Only placement
@@ -55,6 +61,35 @@ class DeviceArena:
         start = max(0, min(start, self.nbytes - nbytes))
         start = start // ALIGN * ALIGN
         return self.buf[start:start + nbytes]
+
+    def split_window(self, main_bytes: int, main_traffic, side_bytes: int):
+        """Two views: `main_bytes` placed as window() places them (the buffers updated in place and the
+        read-only ones), and `side_bytes` for write-only buffers in the region that `main` uses least
+        (the third one, when main straddles the first boundary).  Falls back to one contiguous window
+        (side right behind main) when no such room exists."""
+        main = self.window(main_bytes, main_traffic)
+        lo = main.data_ptr() - self.buf.data_ptr()
+        hi = lo + main_bytes
+        best = None
+        for r in range(3):
+            r0, r1 = r * REGION_BYTES, min((r + 1) * REGION_BYTES, self.nbytes)
+            if r1 - r0 <= 0:
+                continue
+            covered = max(0, min(hi, r1) - max(lo, r0))
+            # the largest free stretch of region r: before or behind main's part of it
+            free = [(r0, max(r0, min(lo, r1))), (min(max(hi, r0), r1), r1)]
+            a, b = max(free, key=lambda ab: ab[1] - ab[0])
+            a = (a + ALIGN - 1) // ALIGN * ALIGN
+            if b - a >= side_bytes and (best is None or covered < best[0]):
+                # a little into the stretch, away from the region's edge, when there is room
+                start = a + min(8 * GIB, (b - a - side_bytes) // 2) // ALIGN * ALIGN
+                best = (covered, start)
+        if best is None or best[0] > 0:
+            whole = self.window(main_bytes + ALIGN + side_bytes,
+                                list(main_traffic or [(main_bytes, 1.0)]) + [(ALIGN + side_bytes, 1.0)])
+            off = (main_bytes + ALIGN - 1) // ALIGN * ALIGN
+            return whole[:main_bytes], whole[off:off + side_bytes]
+        return main, self.buf[best[1]:best[1] + side_bytes]
 
     def verify_regions(self, two_writes, gib_each: int = 2, reps: int = 3, margin: float = 1.08) -> dict:
         """Checks, by timing, that byte offset x of this allocation lies in region x // 96 GiB.

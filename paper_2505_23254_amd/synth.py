@@ -138,20 +138,34 @@ def flat_traffic(n: int, gdt: str = "bf16"):
     return [(e - o, w) for o, e, w in zip(offs, ends, (2.0, 2.0, 2.0, 1.0, 1.0))]
 
 
-def carve_state(n: int, gdt: str, pdt: str, device: str, arena: Optional[torch.Tensor] = None):
+def flat_state_parts(n: int, gdt: str = "bf16"):
+    """(bytes of p | m | v | g, bytes of p_lp) for a state whose parameter copy is placed apart."""
+    offs, sizes, _ = _flat_layout(n, gdt)
+    return max(offs[4], 1), max(sizes[4], 1)
+
+
+def carve_state(n: int, gdt: str, pdt: str, device: str, arena=None):
     """One allocation for a whole optimizer state, cut into p | m | v | g | p_lp in that order.
 
     A single arena keeps the five streams of the update kernel at fixed, known distances from
     each other (the kernel's speed depends on where the streams lie in HBM, and one allocation
     makes that reproducible from process to process).  `arena`: an existing uint8 device buffer
-    of at least flat_state_bytes(n) bytes to cut from, instead of a new allocation.
+    of at least flat_state_bytes(n) bytes to cut from, instead of a new allocation; or a pair of
+    such buffers (flat_state_parts(n) bytes): p | m | v | g from the first, p_lp from the second.
     """
     offs, sizes, total = _flat_layout(n, gdt)
+    dts = [torch.float32, torch.float32, torch.float32, _TORCH_LP[gdt], _TORCH_LP[pdt]]
+    if isinstance(arena, (tuple, list)):
+        main, side = arena
+        if main.dtype != torch.uint8 or side.dtype != torch.uint8 or main.numel() < offs[4] or side.numel() < sizes[4]:
+            raise ValueError("arena pair must be uint8 buffers of at least %d and %d bytes" % (offs[4], sizes[4]))
+        views = [main[o:o + sz].view(dt) for o, sz, dt in zip(offs[:4], sizes[:4], dts[:4])]
+        views.append(side[:sizes[4]].view(dts[4]))
+        return main, views
     if arena is None:
         arena = torch.empty(total, dtype=torch.uint8, device=device)
     elif arena.dtype != torch.uint8 or arena.numel() < total:
         raise ValueError("arena must be a uint8 buffer of at least %d bytes" % total)
-    dts = [torch.float32, torch.float32, torch.float32, _TORCH_LP[gdt], _TORCH_LP[pdt]]
     views = [arena[o:o + sz].view(dt) for o, sz, dt in zip(offs, sizes, dts)]
     return arena, views
 
@@ -162,7 +176,7 @@ def make_flat(cfg: FlatConfig, device: str = "cpu", n: Optional[int] = None,
     for small cases)."""
     n = cfg.n if n is None else n
     if arena is not None:
-        device = arena.device
+        device = arena[0].device if isinstance(arena, (tuple, list)) else arena.device
     gen = torch.Generator(device=device)
     gen.manual_seed(cfg.seed)
     arena, (p, m, v, g, p_lp) = carve_state(n, cfg.gdt, cfg.pdt, device, arena)
@@ -268,6 +282,11 @@ def _tensor_places(shapes, gdt: str = "bf16"):
             total += nbytes
         places.append(row)
     return places, max(total, 1)
+
+
+def list_state_parts(shapes: List[Tuple[str, int]], align_elems: int = 64, gdt: str = "bf16"):
+    """flat_state_parts for a list in layout "streams"."""
+    return flat_state_parts(_list_offsets(shapes, align_elems)[1], gdt)
 
 
 def list_state_bytes(shapes: List[Tuple[str, int]], layout: str = "streams", align_elems: int = 64,

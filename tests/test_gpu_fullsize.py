@@ -167,9 +167,15 @@ def _checksums_list(ls):
     return out
 
 
+def _parts_and_traffic(shapes):
+    parts = synth.list_state_parts(shapes)
+    return parts[0], synth.list_traffic(shapes)[:4], parts[1]
+
+
 def test_llama3_8b_list_every_element():
-    """The benchmark workload itself, as the benchmark lays it out and places it (five flat streams cut
-    from a whole-device allocation, traffic split evenly over two HBM regions): 290 tensors,
+    """The benchmark workload itself, as the benchmark lays it out and places it (flat streams cut from
+    a whole-device allocation: p | m | v | g across the first region boundary, the copy in the third
+    region): 290 tensors,
     8,030,257,152 elements, one scan launch and one gated update launch.  Flag and sum over all
     elements, and EVERY element of p, m, v and the bf16 copy against the oracle: each work item is
     processed exactly once, whichever block draws it."""
@@ -177,17 +183,27 @@ def test_llama3_8b_list_every_element():
     shapes = synth.llama3_8b_shapes()
     cfg = synth.FlatConfig("llama3_8b", 0, seed=3, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
     device_arena = hbm.DeviceArena("cuda", reserve_gib=12)      # the checks below need temporaries
-    nbytes = synth.list_state_bytes(shapes, "streams")
-    window = device_arena.window(nbytes, synth.list_traffic(shapes, "streams"))
-    ls = synth.make_list(shapes, cfg, device="cuda", layout="streams", arena=window)
+    main, side = device_arena.split_window(*_parts_and_traffic(shapes))
+    ls = synth.make_list(shapes, cfg, device="cuda", layout="streams", arena=(main, side))
     n = ls.total
     assert n == 8_030_257_152 and ls.flat.p.numel() == n          # no padding between the views
-    # the state before the step is kept in the part of the allocation behind the window
-    end = window.data_ptr() - device_arena.buf.data_ptr() + nbytes
-    end = (end + hbm.ALIGN - 1) // hbm.ALIGN * hbm.ALIGN
-    if device_arena.nbytes - end < 12 * n:
-        pytest.skip("no room behind the state for a copy of p, m, v")
-    keep = [device_arena.buf[end + 4 * n * k:end + 4 * n * (k + 1)].view(torch.float32) for k in range(3)]
+    base = device_arena.buf.data_ptr()
+    assert (ls.flat.p.data_ptr() - base) // hbm.REGION_BYTES == 0                     # p starts in the first region,
+    assert (ls.flat.v.data_ptr() + 4 * n - base) // hbm.REGION_BYTES == 1              # v ends in the second,
+    assert (ls.flat.p_lp.data_ptr() - base) // hbm.REGION_BYTES == 2                   # the copy lies in the third
+    # the state before the step is kept in what the allocation has left: three stretches, one piece each
+    used = sorted((t.data_ptr() - base, t.data_ptr() - base + t.numel()) for t in (main, side))
+    free, at = [], 0
+    for a, b in used + [(device_arena.nbytes, device_arena.nbytes)]:
+        free.append([(at + hbm.ALIGN - 1) // hbm.ALIGN * hbm.ALIGN, a])
+        at = b
+    keep = []
+    for _ in range(3):
+        spot = next((f for f in free if f[1] - f[0] >= 4 * n), None)
+        if spot is None:
+            pytest.skip("no room beside the state for a copy of p, m, v")
+        keep.append(device_arena.buf[spot[0]:spot[0] + 4 * n].view(torch.float32))
+        spot[0] += (4 * n + hbm.ALIGN - 1) // hbm.ALIGN * hbm.ALIGN
     for dst, src in zip(keep, (ls.flat.p, ls.flat.m, ls.flat.v)):
         dst.copy_(src)
     full = FullCompare(SLAB, "bf16", "bf16", THREADS)
