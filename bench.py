@@ -51,14 +51,14 @@ ACCUM_SOURCES = ("ma_device.h", "ma_internal.h", "ma_norm.hip", "ma_accum.hip")
 STEP_SHA256 = "250b097cc6faf43480ba435598fa58e3c2a693698f5cec00ffca131c49ea7d3c"
 ACCUM_SHA256 = "310a98ba66618c755c626d4298316e786679b0d6f5cf32889dcb49d7964e49d0"
 MEASURED_TRAFFIC = {      # workload: (bytes per launch, sources, their digest when measured)
-    "llama3_8b": (224847235573, STEP_SOURCES, STEP_SHA256),
-    "flat_1e8": (2800296479, STEP_SOURCES, STEP_SHA256),
-    "fp16_5e7": (1400284392, STEP_SOURCES, STEP_SHA256),
-    "fp32grad_8b": (240908651118, STEP_SOURCES, STEP_SHA256),
-    "auto_fp16_8b": (224847203550, STEP_SOURCES, STEP_SHA256),
-    "qwen14b_4sub": (87973268477, STEP_SOURCES, STEP_SHA256),
-    "bf16_states_8b": (112423817570, STEP_SOURCES, STEP_SHA256),
-    "accumulate_8b": (80301732827, ACCUM_SOURCES, ACCUM_SHA256),
+    "llama3_8b": (224847078149, STEP_SOURCES, STEP_SHA256),
+    "flat_1e8": (2800289609, STEP_SOURCES, STEP_SHA256),
+    "fp16_5e7": (1400289133, STEP_SOURCES, STEP_SHA256),
+    "fp32grad_8b": (240908583225, STEP_SOURCES, STEP_SHA256),
+    "auto_fp16_8b": (224847162007, STEP_SOURCES, STEP_SHA256),
+    "qwen14b_4sub": (87973208469, STEP_SOURCES, STEP_SHA256),
+    "bf16_states_8b": (112423906640, STEP_SOURCES, STEP_SHA256),
+    "accumulate_8b": (80301737055, ACCUM_SOURCES, ACCUM_SHA256),
 }
 
 
