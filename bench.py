@@ -20,7 +20,8 @@ gradients, clip 1.0; --layout tensor|streams), flat_1e8, fp16_5e7, c1, c1_onecal
 sub-groups streamed on one stream); rows beyond the basic step at the 8B element count:
 fp32grad_8b (the 8B list with fp32 gradients: the accumulated flat buffer of Sec. III-C as input,
 4 + 30 B/param), bf16_states_8b (p/m/v held in bf16, truncating stores, 14 B/param), accumulate_8b (4 bf16
-micro-batch gradients into the fp32 flat buffer, 6 / 10 B/param), auto_fp16_8b (fp16 gradients,
+micro-batch gradients into the fp32 flat buffer, 6 / 10 B/param), accumulate1_8b (one micro-batch per
+step: the overwrite fused with the scan), auto_fp16_8b (fp16 gradients,
 loss scale, update number and gate all read on the device).
 """
 import argparse
@@ -59,6 +60,7 @@ MEASURED_TRAFFIC = {      # workload: (bytes per launch, sources, their digest w
     "qwen14b_4sub": (87973208469, STEP_SOURCES, STEP_SHA256),
     "bf16_states_8b": (112423906640, STEP_SOURCES, STEP_SHA256),
     "accumulate_8b": (80301737055, ACCUM_SOURCES, ACCUM_SHA256),
+    "accumulate1_8b": (48181473391, ACCUM_SOURCES, ACCUM_SHA256),
 }
 
 
@@ -71,6 +73,7 @@ TRAFFIC_SOURCE = {
     "qwen14b_4sub": "profiles/step_and_norm_flat_kernels__qwen14b_4sub.txt",
     "bf16_states_8b": "profiles/step_flat_kernel_bf16_states__bf16_states_8b.txt",
     "accumulate_8b": "profiles/accumulate_kernel__accumulate_8b.txt",
+    "accumulate1_8b": "profiles/accumulate_kernel_overwrite_scan__accumulate1_8b.txt",
 }
 
 
@@ -167,7 +170,7 @@ class Workload:
             self.parts = ma.new_result(4)
             self.desc = ("14B-class list (%d elements) as 4 equal flat sub-groups streamed on one "
                          "stream, bf16 grads, clip 1.0" % total)
-        elif name in ("bf16_states_8b", "accumulate_8b"):
+        elif name in ("bf16_states_8b", "accumulate_8b", "accumulate1_8b"):
             # flat sub-groups of the 8B element count for the rows beyond the basic step
             n = sum(k for _, k in synth.llama3_8b_shapes())
             cfg = synth.FlatConfig(name, n, seed=5, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
@@ -181,11 +184,16 @@ class Workload:
             else:
                 sizes, weights = [up(4 * n), up(2 * n)], (2.0, 1.0)
                 self.step_bytes, self.kind = 10.0, "accum"
-                self.micro = 4
+                self.micro = 4 if name == "accumulate_8b" else 1
                 self.kernel_label = "gradient accumulation into the fp32 flat buffer (2nd and later micro-batches)"
                 self.desc = ("fp32 flat gradient buffer n=%d, %d bf16 micro-batch gradients per step "
                              "(first overwrites, the others add, the last add is fused with the "
                              "overflow / norm scan of the buffer)" % (n, self.micro))
+                if self.micro == 1:      # one micro-batch per iteration: the overwrite itself carries the scan
+                    self.step_bytes = 6.0
+                    self.kernel_label = "overwrite of the fp32 flat buffer fused with the overflow / norm scan"
+                    self.desc = ("fp32 flat gradient buffer n=%d, one bf16 micro-batch gradient per step: "
+                                 "overwrite fused with the overflow / norm scan of the buffer" % n)
             buf = place(sum(sizes), list(zip(sizes, weights)))
             if buf is None:
                 buf = torch.empty(sum(sizes), dtype=torch.uint8, device="cuda")
@@ -267,6 +275,10 @@ class Workload:
                 ev[1].record()
             ma.adamw_step_bf16_gated(self.bp, self.bm, self.bv, self.bg, self.h, self.t, c.loss_scale,
                                      self.res, c.max_norm)
+        elif self.kind == "accum" and self.micro == 1:
+            if record:
+                ev[1].record()
+            ma.grad_accumulate_scan(self.acc, self.bg, True, c.loss_scale, self.res, self.ws)
         elif self.kind == "accum":
             ma.grad_accumulate(self.acc, self.bg, first=True)
             if record:
@@ -386,18 +398,22 @@ def summarise(wl, ma, ms_per_step, quiet=False):
     if not quiet:
         log("2nd phase ms per step: " + " ".join("%.3f" % e[1].elapsed_time(e[2]) for e in wl.events))
         log("1st phase ms per step: " + " ".join("%.3f" % e[0].elapsed_time(e[1]) for e in wl.events))
-    if wl.kind != "accum":
+    if wl.kind != "accum" or wl.micro == 1:
         ov, ss = ma.read_result(wl.res)
         if ov:
             sys.exit("bench.py: unexpected overflow flag on clean synthetic gradients (%s)" % wl.name)
     else:
         ss = None
     # launches of the dominant kernel in the second phase of a step, and what precedes them
-    launches = {"sub": 4, "accum": wl.micro - 1 if wl.kind == "accum" else 1}.get(wl.kind, 1)
+    launches = {"sub": 4, "accum": max(1, wl.micro - 1) if wl.kind == "accum" else 1}.get(wl.kind, 1)
     passes = launches if wl.kind == "accum" else 1          # times the second phase sweeps all n elements
     achieved = wl.step_bytes * wl.n * passes / (rest_ms * 1e-3) / 1e9
     gdt_bytes = 4.0 if wl.cfg.gdt == "f32" else 2.0
-    if wl.kind == "accum":
+    if wl.kind == "accum" and wl.micro == 1:
+        first = None
+        value = wl.n / (ms_per_step * 1e-3) / 1e9
+        whole = 6.0 * wl.n / (ms_per_step * 1e-3) / 1e9
+    elif wl.kind == "accum":
         first = {"kernel": "first micro-batch (overwrite)", "avg_ms": first_ms, "bytes_per_param": 6.0,
                  "achieved": 6.0 * wl.n / (first_ms * 1e-3) / 1e9}
         value = wl.n * wl.micro / (ms_per_step * 1e-3) / 1e9       # micro-batch elements accumulated
@@ -461,7 +477,7 @@ def release(wl):
 # The other workloads a default run reports under "also": (name, timed steps, warm-up steps, rotate).
 ALSO = (("c1", 400, 40, 32), ("c1_onecall", 400, 40, 32), ("flat_1e8", 100, 10, 1), ("fp16_5e7", 100, 10, 1), ("qwen14b_4sub", 8, 2, 1),
         ("fp32grad_8b", 8, 2, 1), ("auto_fp16_8b", 8, 2, 1), ("bf16_states_8b", 10, 2, 1),
-        ("accumulate_8b", 5, 2, 1))
+        ("accumulate_8b", 5, 2, 1), ("accumulate1_8b", 8, 2, 1))
 
 
 def main():
@@ -471,7 +487,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=None,
                     choices=["llama3_8b", "fp32grad_8b", "flat_1e8", "fp16_5e7", "c1", "c1_onecall", "qwen14b_4sub",
-                             "bf16_states_8b", "accumulate_8b", "auto_fp16_8b"],
+                             "bf16_states_8b", "accumulate_8b", "accumulate1_8b", "auto_fp16_8b"],
                     help="default: llama3_8b, followed by short runs of all the others (see --also)")
     ap.add_argument("--also", default=None, choices=["all", "none"],
                     help="after the timed region also run the other workloads, the plain-placement run and "
