@@ -12,7 +12,8 @@ bounded sample of the same workload.
 
 With no --workload the line describes the 8B-shaped list (K timed steps) and carries, measured in the
 same process after the timed region: "also" = the other workloads below (their own short runs),
-roofline.frac_plain = the same kernel with the state in an ordinary allocation, and
+roofline.frac_plain = the same kernel with the state in an ordinary allocation,
+roofline.frac_stitched = with the state in a range that ma_arena_create maps from classified blocks, and
 roofline.mix_ceiling_GBps = what a trivial kernel with the same stream mix reaches on the same buffers.
 
 Workloads: llama3_8b (default; 290-tensor Llama-3-8B-shaped list, 8.03e9 elements, bf16
@@ -105,9 +106,11 @@ class Workload:
         # arena: an hbm.DeviceArena (placement "region": the state is cut from one whole-device
         # allocation: p | m | v | g at the offset that splits their traffic evenly over two of the three
         # 96 GiB HBM regions, the write-only parameter copy in the third), or None (placement "plain":
-        # a fresh allocation of just the state's size, wherever the driver puts it)
+        # a fresh allocation of just the state's size, wherever the driver puts it), or an
+        # hbm.StitchedArena (placement "stitched": the same split over three regions, but only the state's
+        # bytes, mapped from physical blocks that the library classified by timing)
         self.name, self.ma, self.layout = name, ma, "flat"
-        self.placement = "region" if arena is not None else "plain"
+        self.placement = arena.placement if arena is not None else "plain"
         self.device_arena = arena
         def place(nbytes, traffic):
             if self.device_arena is None:
@@ -465,8 +468,12 @@ def mix_ceiling(wl, ma, reps=5):
     return best
 
 
-def release(wl):
+def release(wl, arena_too=False):
     import gc
+    held = getattr(wl, "device_arena", None)
+    if held is not None and (arena_too or held.placement == "stitched"):
+        torch.cuda.synchronize()
+        held.release()      # a stitched range is per workload; the whole-device arena is shared
     for a in ("state", "plan", "flat", "flats", "raw", "bp", "bm", "bv", "bg", "acc", "device_arena"):
         if hasattr(wl, a):
             setattr(wl, a, None)
@@ -495,9 +502,11 @@ def main():
     ap.add_argument("--layout", default="streams", choices=["streams", "tensor"],
                     help="llama3_8b only: how the list's buffers lie in the state: 'streams' = five flat "
                          "buffers p|m|v|g|p_lp (default), 'tensor' = the five buffers of each tensor adjacent")
-    ap.add_argument("--placement", default="region", choices=["region", "plain"],
+    ap.add_argument("--placement", default="region", choices=["region", "stitched", "plain"],
                     help="'region' (default): cut the state from one whole-device allocation so that its "
-                         "traffic splits evenly over two 96 GiB HBM regions; 'plain': a fresh allocation")
+                         "traffic splits evenly over two 96 GiB HBM regions; 'stitched': the same split, but "
+                         "only the state's bytes, mapped by ma_arena_create from physical blocks whose region "
+                         "it finds by timing; 'plain': a fresh allocation")
     ap.add_argument("--rotate", type=int, default=1, metavar="K",
                     help="flat_1e8 / fp16_5e7 / c1 only: step K distinct sub-groups of the workload's shape in "
                          "turn, so that a small sub-group is read from HBM rather than from the caches")
@@ -533,6 +542,8 @@ def main():
         except RuntimeError as e:      # e.g. another process holds most of the device
             log("bench.py: whole-device arena not available (%s); falling back to a plain allocation" % e)
             arena = None
+    elif args.placement == "stitched":
+        arena = hbm.StitchedArena(ma.Arena)
     t_setup = time.perf_counter()
     wl = Workload(name, ma, args.layout, arena, max(1, args.rotate))
     torch.cuda.synchronize()
@@ -542,7 +553,7 @@ def main():
 
     if args.copy_calibration > 0:
         nb = args.copy_calibration
-        if wl.device_arena is not None:      # the arena holds the device's memory: use its unused tail
+        if wl.placement == "region":         # the arena holds the device's memory: use its unused tail
             buf = wl.device_arena.buf
             fl = wl.state.flat if wl.kind in ("multi", "auto") else getattr(wl, "flat", None)
             used = [wl.raw] if wl.kind in ("bf16", "accum") else \
@@ -573,7 +584,7 @@ def main():
         "config": {"workload": name, "description": wl.desc, "elements": wl.n,
                    "layout": wl.layout, "placement": wl.placement,
                    "placement_verified": None if verify is None or wl.placement != "region" else verify["verified"],
-                   "placement_check": verify,
+                   "placement_check": verify if wl.placement != "stitched" else wl.device_arena.report,
                    "rotating_sets": len(getattr(wl, "flats", None) or [None]),
                    "grad_dtype": wl.cfg.gdt, "param_copy_dtype": wl.cfg.pdt,
                    "max_norm": wl.cfg.max_norm, "loss_scale": wl.cfg.loss_scale,
@@ -626,6 +637,18 @@ def main():
             log("plain placement: %.3f ms/step, update %.0f GB/s (%.1f %%), mix ceiling %s GB/s"
                 % (ms3, r3["achieved"], 100 * r3["frac"], roofline["plain"]["mix_ceiling_GBps"]))
             release(w3)
+            # and in a range of just the state's size that the library stitches from classified blocks
+            st = hbm.StitchedArena(ma.Arena)
+            w4 = Workload(name, ma, args.layout, st, 1)
+            ms4 = run(w4, 8, 2)
+            v4, r4, _ = summarise(w4, ma, ms4, quiet=True)
+            roofline["frac_stitched"] = r4["frac"]
+            roofline["stitched"] = {"placement": w4.placement, "ms_per_step": ms4, "value": v4,
+                                    "achieved": r4["achieved"], "avg_launch_ms": r4["avg_launch_ms"],
+                                    "arena": st.report}
+            log("stitched placement: %.3f ms/step, update %.0f GB/s (%.1f %%), %s"
+                % (ms4, r4["achieved"], 100 * r4["frac"], st.report))
+            release(w4)
         log("extras took %.1f s" % (time.perf_counter() - t_extra))
     print(json.dumps(out), flush=True)
 

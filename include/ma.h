@@ -18,7 +18,8 @@
  *
  * Conventions that hold for every entry point
  *   - All data pointers are DEVICE pointers owned by the caller, unless the name ends in _host.
- *     The library never allocates, frees or keeps device memory.
+ *     The library never allocates, frees or keeps device memory (the placement helper ma_arena_*
+ *     at the end of this header is the one exception: allocating is what it is for).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
  *     enqueued on it; results are valid once the stream has been synchronised.  No entry point
  *     synchronises the device, except ma_multi_prepare (documented there).
@@ -438,6 +439,40 @@ int ma_probe_update_mix(void* a, void* b, void* c, const void* d16, void* e16, s
  * streams in different regions, so timing this call at chosen offsets of a large allocation shows how
  * the allocation maps onto the regions. */
 int ma_probe_two_writes(void* x, void* y, size_t bytes_each, void* stream);
+
+/* ---- placement helper: device memory for one state, stitched from blocks of known HBM regions ------ */
+
+/* The only calls of this library that allocate device memory; they exist to do so.  Where a state
+ * lies physically decides ~4 % of the update kernel's rate (Sec. II-A: the step is memory-bound): best
+ * measured is p | m | v | g with half of their traffic in one 96 GiB region of the HBM and half in
+ * another, and the write-only parameter copy in a third.  ma_arena_create builds such a range with
+ * the virtual-memory API: it creates physical blocks of block_bytes one by one, finds each block's
+ * region by timing two write streams against the first block of every region seen so far, maps
+ *     [first_region_bytes of main | rest of main | side]
+ * from three different regions into ONE contiguous address range, and returns every block it does
+ * not need to the driver.  On a fresh device physical memory is handed out region after region, so
+ * reaching a second or third region means creating blocks worth the ones before; max_transient_bytes
+ * bounds what may be held at once (0: just main + side, i.e. whatever regions come first).  When the
+ * wanted regions cannot be had, the parts are filled from what there is; ma_arena_get_report says
+ * how many blocks of each part lie where they were wanted.
+ *   main_bytes > 0; first_region_bytes <= main_bytes: where main's traffic midpoint lies (rounded to
+ *   blocks); side_bytes may be 0; block_bytes: 0 = 1 GiB, else a multiple of 2 MiB >= 64 MiB (smaller
+ *   blocks are timed less reliably).  Creation synchronises the device and takes a few
+ *   milliseconds per block.  The arena belongs to the device current at creation. */
+typedef struct ma_arena ma_arena;
+typedef struct ma_arena_report {
+  uint64_t main_bytes, side_bytes, first_region_bytes; /* as mapped (whole blocks) */
+  uint64_t blocks_created;                              /* physical blocks created while searching */
+  uint64_t first_blocks_in_place, second_blocks_in_place, side_blocks_in_place;
+  uint32_t regions_seen;
+  float same_region_GBps; /* this machine's rate of two write streams inside one block */
+} ma_arena_report;
+int ma_arena_create(size_t main_bytes, size_t first_region_bytes, size_t side_bytes, size_t block_bytes,
+                    size_t max_transient_bytes, ma_arena** arena_out);
+void* ma_arena_main(const ma_arena* arena); /* device address of the main part */
+void* ma_arena_side(const ma_arena* arena); /* device address of the side part, NULL if side_bytes was 0 */
+int ma_arena_get_report(const ma_arena* arena, ma_arena_report* out_host);
+int ma_arena_destroy(ma_arena* arena);      /* unmaps and releases everything; NULL is allowed */
 
 #ifdef __cplusplus
 }

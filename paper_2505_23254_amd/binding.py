@@ -68,6 +68,14 @@ class MultiPlanStruct(ctypes.Structure):
                 ("magic", ctypes.c_uint32), ("sdt", ctypes.c_uint32)]
 
 
+class ArenaReport(ctypes.Structure):
+    _fields_ = [("main_bytes", ctypes.c_uint64), ("side_bytes", ctypes.c_uint64),
+                ("first_region_bytes", ctypes.c_uint64), ("blocks_created", ctypes.c_uint64),
+                ("first_blocks_in_place", ctypes.c_uint64), ("second_blocks_in_place", ctypes.c_uint64),
+                ("side_blocks_in_place", ctypes.c_uint64), ("regions_seen", ctypes.c_uint32),
+                ("same_region_GBps", ctypes.c_float)]
+
+
 def _load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(
@@ -122,6 +130,11 @@ def _load() -> ctypes.CDLL:
         "ma_probe_update_mix": ([vp, vp, vp, vp, vp, sz, i32, vp], ctypes.c_int),
         "ma_probe_two_writes": ([vp, vp, sz, vp], ctypes.c_int),
         "ma_multi_adamw_step_auto": ([vp, vp, vp, vp, f32, vp], ctypes.c_int),
+        "ma_arena_create": ([sz, sz, sz, sz, sz, vp], ctypes.c_int),
+        "ma_arena_main": ([vp], vp),
+        "ma_arena_side": ([vp], vp),
+        "ma_arena_get_report": ([vp, vp], ctypes.c_int),
+        "ma_arena_destroy": ([vp], ctypes.c_int),
     }
     for name, (args, res) in sig.items():
         fn = getattr(lib, name)
@@ -540,3 +553,39 @@ def pinned_alloc(nbytes: int) -> int:
 
 def pinned_free(ptr: int) -> None:
     _check(lib.ma_pinned_free(ptr))
+
+
+class _RawDeviceBytes:
+    """A device address range offered to torch through the CUDA array interface."""
+
+    def __init__(self, ptr: int, nbytes: int, owner):
+        self.owner = owner
+        self.__cuda_array_interface__ = {"shape": (nbytes,), "typestr": "|u1", "data": (ptr, False),
+                                         "version": 3, "strides": None}
+
+
+class Arena:
+    """ma_arena_create: `main_bytes` (+ `side_bytes`) of device memory stitched from physical blocks so
+    that the first `first_region_bytes` of main, the rest of main and the side part lie in three
+    different HBM regions.  `.main` / `.side` are uint8 tensors over the two parts (views: they do not
+    own the memory; call close() only after the last use of them)."""
+
+    def __init__(self, main_bytes: int, first_region_bytes: int, side_bytes: int = 0,
+                 block_bytes: int = 0, max_transient_bytes: int = 0):
+        h = ctypes.c_void_p()
+        _check(lib.ma_arena_create(main_bytes, first_region_bytes, side_bytes, block_bytes,
+                                   max_transient_bytes, ctypes.byref(h)))
+        self._h = h
+        rep = ArenaReport()
+        _check(lib.ma_arena_get_report(h, ctypes.byref(rep)))
+        self.report = {k: getattr(rep, k) for k, _ in ArenaReport._fields_}
+        self.main = torch.as_tensor(_RawDeviceBytes(lib.ma_arena_main(h), main_bytes, self), device="cuda")
+        self.side = (torch.as_tensor(_RawDeviceBytes(lib.ma_arena_side(h), side_bytes, self), device="cuda")
+                     if side_bytes else None)
+
+    def close(self):
+        if self._h:
+            torch.cuda.synchronize()
+            self.main = self.side = None
+            _check(lib.ma_arena_destroy(self._h))
+            self._h = None

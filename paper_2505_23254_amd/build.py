@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OUT = os.path.join(HERE, "libma_step.so")
-SOURCES = ["ma_api.hip", "ma_norm.hip", "ma_adamw.hip", "ma_accum.hip", "ma_probe.hip", "ma_pool.cpp"]
+SOURCES = ["ma_api.hip", "ma_norm.hip", "ma_adamw.hip", "ma_accum.hip", "ma_probe.hip", "ma_arena.hip", "ma_pool.cpp"]
 HEADERS = ["ma_device.h", "ma_internal.h", os.path.join("..", "..", "include", "ma.h")]
 
 # -ffp-contract=off: the update kernel states every fused multiply-add itself.

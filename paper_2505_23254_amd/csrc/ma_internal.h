@@ -45,6 +45,9 @@ hipError_t launch_step(const Desc* row_host, const Desc* table_dev, uint32_t row
                        int sdt, int gdt, int pdt, const StepScalars& s, const StepControl& ctl,
                        StepQueue* queue, int device_cus, hipStream_t stream);
 
+// Two write-only streams of bytes_each bytes (the measurement aid behind ma_probe_two_writes).
+hipError_t launch_probe_two_writes(void* x, void* y, size_t bytes_each, hipStream_t stream);
+
 // A tensor list's device table: the counters, then one row per non-empty tensor.
 constexpr size_t kTableHeadBytes = sizeof(StepQueue);
 

@@ -100,6 +100,15 @@ __global__ __launch_bounds__(kBlock) void probe_two_writes_kernel(f32x4* x_, f32
   }
 }
 
+hipError_t launch_probe_two_writes(void* x, void* y, size_t bytes_each, hipStream_t stream) {
+  int dev = 0, cus = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return e;
+  probe_two_writes_kernel<<<cus * 4, kBlock, 0, stream>>>(static_cast<f32x4*>(x), static_cast<f32x4*>(y), bytes_each / 16);
+  return hipGetLastError();
+}
+
 }  // namespace ma
 
 // error channel of the library (ma_api.hip)

@@ -19,8 +19,10 @@ Measured on MI355X (two-stream write and mixed read/write probes over a whole-de
   memory system rewards is write traffic spread over more regions than the reads.
 
 Hence this helper: take the device's free memory as one arena and hand out, for a state of a given
-size, the window of the arena whose traffic midpoint sits on a region boundary.  Only placement
-lives here; nothing of the optimizer step.
+size, the window of the arena whose traffic midpoint sits on a region boundary (DeviceArena).  A
+caller that cannot give the whole device away gets the same placement from StitchedArena: just the
+state's bytes, built by the library's ma_arena_create from physical blocks whose region it finds by
+timing.  Only placement lives here; nothing of the optimizer step.
 """
 from typing import Optional, Sequence, Tuple
 
@@ -125,6 +127,11 @@ class DeviceArena:
         return {"verified": bool(min(c) >= margin * max(s)), "same_GBps": [round(x) for x in s],
                 "cross_GBps": [round(x) for x in c], "pairs_GiB": {"same": same, "cross": cross}}
 
+    placement = "region"
+
+    def release(self):
+        self.buf = None
+
     @staticmethod
     def _midpoint(nbytes: int, traffic) -> int:
         if not traffic:
@@ -137,3 +144,44 @@ class DeviceArena:
             acc += b * w
             off += b
         return nbytes // 2
+
+
+class StitchedArena:
+    """The placement of DeviceArena without holding the device: every request builds an address range
+    of just the requested size out of 1-GiB physical blocks (`make_arena` = the binding's Arena, i.e.
+    ma_arena_create): the part of `main` before its traffic midpoint from one region, the rest from
+    another, the write-only `side` part from a third.  While it searches it holds at most
+    `max_transient_bytes` (default: all free memory but `reserve_gib`), a fraction of a second; the
+    blocks it does not use go back to the driver.  One request is alive at a time: the next request, or
+    release(), unmaps the previous one (its views must not be used after that)."""
+
+    placement = "stitched"
+
+    def __init__(self, make_arena, max_transient_bytes: Optional[int] = None, reserve_gib: float = 3.0,
+                 block_bytes: int = 0):
+        self.make_arena, self.max_transient, self.reserve = make_arena, max_transient_bytes, reserve_gib
+        self.block_bytes = block_bytes
+        self.current = None
+        self.report = None
+
+    def _build(self, main_bytes, first, side_bytes):
+        self.release()
+        limit = self.max_transient
+        if limit is None:
+            free, _ = torch.cuda.mem_get_info()
+            limit = max(0, int(free - self.reserve * GIB))
+        self.current = self.make_arena(main_bytes, first, side_bytes, self.block_bytes, limit)
+        self.report = dict(self.current.report)
+        return self.current
+
+    def window(self, nbytes: int, traffic=None) -> torch.Tensor:
+        return self._build(nbytes, DeviceArena._midpoint(nbytes, traffic), 0).main
+
+    def split_window(self, main_bytes: int, main_traffic, side_bytes: int):
+        a = self._build(main_bytes, DeviceArena._midpoint(main_bytes, main_traffic), side_bytes)
+        return a.main, a.side
+
+    def release(self):
+        if self.current is not None:
+            self.current.close()
+            self.current = None

@@ -450,3 +450,19 @@ def test_probe_argument_errors():
     assert g(A, None, 1 << 20, None) == ma.MA_ERR_NULL
     assert g(A, A + 8, 1 << 20, None) == ma.MA_ERR_ALIGN
     assert g(A, A, 1024, None) == ma.MA_ERR_ARG
+
+
+def test_arena_argument_errors():
+    """ma_arena_create turns down what it cannot build before it touches the device."""
+    f = ma.lib.ma_arena_create
+    h = ctypes.c_void_p()
+    GIB = 1 << 30
+    assert f(GIB, GIB // 2, 0, 0, 0, None) == ma.MA_ERR_NULL
+    assert f(0, 0, 0, 0, 0, ctypes.byref(h)) == ma.MA_ERR_ARG
+    assert f(GIB, 2 * GIB, 0, 0, 0, ctypes.byref(h)) == ma.MA_ERR_ARG and b"first_region_bytes" in ma.lib.ma_last_error()
+    assert f(GIB, 0, 0, 3 << 20, 0, ctypes.byref(h)) == ma.MA_ERR_ARG          # block below 64 MiB
+    assert f(GIB, 0, 0, (64 << 20) + 4096, 0, ctypes.byref(h)) == ma.MA_ERR_ARG  # not a multiple of 2 MiB
+    assert h.value is None
+    assert ma.lib.ma_arena_destroy(None) == ma.MA_OK
+    assert ma.lib.ma_arena_main(None) is None and ma.lib.ma_arena_side(None) is None
+    assert ma.lib.ma_arena_get_report(None, None) == ma.MA_ERR_NULL

@@ -81,3 +81,40 @@ def test_small_states_and_small_arenas():
     main, side = small.split_window(parts[0], traffic, parts[1])
     (a, b), (c, d) = _span(small, main), _span(small, side)
     assert 0 <= a and b <= c and d <= small.nbytes and c - b < 2 * hbm.ALIGN
+
+
+def test_stitched_arena_requests_the_traffic_midpoint(monkeypatch):
+    """StitchedArena asks the allocator for main cut at its traffic midpoint, keeps one request alive at
+    a time and closes the previous one."""
+    made, closed = [], []
+
+    class _Made:
+        def __init__(self, *args):
+            made.append(args)
+            self.report = {"regions_seen": 3}
+            self.main, self.side = _View(0, args[0]), _View(0, args[2]) if args[2] else None
+
+        def close(self):
+            closed.append(self)
+
+    st = hbm.StitchedArena(_Made, max_transient_bytes=200 * GIB)
+    shapes = synth.llama3_8b_shapes()
+    parts, traffic = synth.list_state_parts(shapes), synth.list_traffic(shapes)
+    main, side = st.split_window(parts[0], traffic[:4], parts[1])
+    main_bytes, first, side_bytes, block, limit = made[-1]
+    assert (main_bytes, side_bytes, block, limit) == (parts[0], parts[1], 0, 200 * GIB)
+    # half of the traffic of p | m | v | g lies before `first`
+    below = total = 0.0
+    off = 0
+    for nb, w in traffic[:4]:
+        below += w * max(0, min(off + nb, first) - off)
+        total += w * nb
+        off += nb
+    assert abs(below / total - 0.5) < 1e-6
+    assert main.numel() == parts[0] and side.numel() == parts[1] and st.report == {"regions_seen": 3}
+    w = st.window(10 * GIB, None)                       # a new request closes the one before
+    assert len(closed) == 1 and made[-1][:3] == (10 * GIB, 5 * GIB, 0) and w.numel() == 10 * GIB
+    st.release()
+    assert len(closed) == 2 and st.current is None
+    st.release()                                        # idempotent
+    assert len(closed) == 2
