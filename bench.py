@@ -539,6 +539,14 @@ def main():
             verify = arena.verify_regions(ma.probe_two_writes)
             log("placement check (two write streams, GB/s): same region %s, different regions %s -> %s"
                 % (verify["same_GBps"], verify["cross_GBps"], "verified" if verify["verified"] else "NOT verified"))
+            if not verify["verified"]:
+                # this allocation does not map onto the regions as assumed: let the library find the
+                # regions block by block instead
+                log("bench.py: switching to the stitched placement (ma_arena_create)")
+                arena.release()
+                arena = None
+                torch.cuda.empty_cache()
+                arena = hbm.StitchedArena(ma.Arena)
         except RuntimeError as e:      # e.g. another process holds most of the device
             log("bench.py: whole-device arena not available (%s); falling back to a plain allocation" % e)
             arena = None
@@ -584,7 +592,8 @@ def main():
         "config": {"workload": name, "description": wl.desc, "elements": wl.n,
                    "layout": wl.layout, "placement": wl.placement,
                    "placement_verified": None if verify is None or wl.placement != "region" else verify["verified"],
-                   "placement_check": verify if wl.placement != "stitched" else wl.device_arena.report,
+                   "placement_check": verify,
+                   "stitched_arena": wl.device_arena.report if wl.placement == "stitched" else None,
                    "rotating_sets": len(getattr(wl, "flats", None) or [None]),
                    "grad_dtype": wl.cfg.gdt, "param_copy_dtype": wl.cfg.pdt,
                    "max_norm": wl.cfg.max_norm, "loss_scale": wl.cfg.loss_scale,
