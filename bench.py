@@ -50,18 +50,18 @@ SCAN_BYTES_PER_PARAM = 2.0     # scan kernel: read g
 # kernels are built from differs, the figure is reported as null.
 STEP_SOURCES = ("ma_device.h", "ma_internal.h", "ma_norm.hip", "ma_adamw.hip")
 ACCUM_SOURCES = ("ma_device.h", "ma_internal.h", "ma_norm.hip", "ma_accum.hip")
-STEP_SHA256 = "250b097cc6faf43480ba435598fa58e3c2a693698f5cec00ffca131c49ea7d3c"
-ACCUM_SHA256 = "310a98ba66618c755c626d4298316e786679b0d6f5cf32889dcb49d7964e49d0"
+STEP_SHA256 = "89c2b05c0092404313d34a01e6d704e58e6833b33dc7fa1c83da8aa9318592f1"
+ACCUM_SHA256 = "db74af454226034f9c1f11421ec1510a983596dffcaefeabd12dfe2997cc1086"
 MEASURED_TRAFFIC = {      # workload: (bytes per launch, sources, their digest when measured)
-    "llama3_8b": (224847078149, STEP_SOURCES, STEP_SHA256),
-    "flat_1e8": (2800289609, STEP_SOURCES, STEP_SHA256),
-    "fp16_5e7": (1400289133, STEP_SOURCES, STEP_SHA256),
-    "fp32grad_8b": (240908583225, STEP_SOURCES, STEP_SHA256),
-    "auto_fp16_8b": (224847162007, STEP_SOURCES, STEP_SHA256),
-    "qwen14b_4sub": (87973208469, STEP_SOURCES, STEP_SHA256),
-    "bf16_states_8b": (112423906640, STEP_SOURCES, STEP_SHA256),
-    "accumulate_8b": (80301737055, ACCUM_SOURCES, ACCUM_SHA256),
-    "accumulate1_8b": (48181473391, ACCUM_SOURCES, ACCUM_SHA256),
+    "llama3_8b": (224846802593, STEP_SOURCES, STEP_SHA256),
+    "flat_1e8": (2800316069, STEP_SOURCES, STEP_SHA256),
+    "fp16_5e7": (1400328248, STEP_SOURCES, STEP_SHA256),
+    "fp32grad_8b": (240908631374, STEP_SOURCES, STEP_SHA256),
+    "auto_fp16_8b": (224846774094, STEP_SOURCES, STEP_SHA256),
+    "qwen14b_4sub": (87972968465, STEP_SOURCES, STEP_SHA256),
+    "bf16_states_8b": (112423623710, STEP_SOURCES, STEP_SHA256),
+    "accumulate_8b": (80301727132, ACCUM_SOURCES, ACCUM_SHA256),
+    "accumulate1_8b": (48181468849, ACCUM_SOURCES, ACCUM_SHA256),
 }
 
 
