@@ -152,6 +152,12 @@ int ma_arena_create(size_t main_bytes, size_t first_region_bytes, size_t side_by
     for (size_t r = 0; r < ref.size() && region < 0 && rc == MA_OK; ++r) {
       float g = 0.0f;
       rc = pair_rate(staging + slot * B, staging + ref[r] * B, B, &g);
+      // a rate near the threshold is measured again (a slow outlier must not merge two regions)
+      for (int again = 0; again < 2 && rc == MA_OK && g > 0.94f * threshold && g < 1.06f * threshold; ++again) {
+        float g2 = 0.0f;
+        rc = pair_rate(staging + slot * B, staging + ref[r] * B, B, &g2);
+        g = std::max(g, g2);
+      }
       if (rc == MA_OK && g < threshold) region = int(r);
     }
     if (region < 0) {
