@@ -12,8 +12,7 @@ bounded sample of the same workload.
 
 With no --workload the line describes the 8B-shaped list (K timed steps) and carries, measured in the
 same process after the timed region: "also" = the other workloads below (their own short runs),
-roofline.frac_plain = the same kernel with the state in an ordinary allocation,
-roofline.frac_stitched = with the state in a range that ma_arena_create maps from classified blocks, and
+roofline.frac_plain = the same kernel with the state in an ordinary allocation, and
 roofline.mix_ceiling_GBps = what a trivial kernel with the same stream mix reaches on the same buffers.
 
 Workloads: llama3_8b (default; 290-tensor Llama-3-8B-shaped list, 8.03e9 elements, bf16
@@ -103,12 +102,12 @@ class Workload:
     """Holds device state and enqueues one step; records (scan, update) event pairs."""
 
     def __init__(self, name, ma, layout="streams", arena=None, rotate=1):
-        # arena: an hbm.DeviceArena (placement "region": the state is cut from one whole-device
-        # allocation: p | m | v | g at the offset that splits their traffic evenly over two of the three
-        # 96 GiB HBM regions, the write-only parameter copy in the third), or None (placement "plain":
-        # a fresh allocation of just the state's size, wherever the driver puts it), or an
-        # hbm.StitchedArena (placement "stitched": the same split over three regions, but only the state's
-        # bytes, mapped from physical blocks that the library classified by timing)
+        # arena: an hbm.StitchedArena (placement "stitched": the state is cut from a range that the
+        # library mapped from physical blocks of known HBM region: p | m | v | g at the offset that splits
+        # their traffic evenly over two of the three 96 GiB regions, the write-only parameter copy in
+        # the third), an hbm.DeviceArena (placement "region": the same cut from one whole-device
+        # allocation), or None (placement "plain": a fresh allocation of just the state's size,
+        # wherever the driver puts it)
         self.name, self.ma, self.layout = name, ma, "flat"
         self.placement = arena.placement if arena is not None else "plain"
         self.device_arena = arena
@@ -468,17 +467,60 @@ def mix_ceiling(wl, ma, reps=5):
     return best
 
 
-def release(wl, arena_too=False):
+def release(wl):
     import gc
-    held = getattr(wl, "device_arena", None)
-    if held is not None and (arena_too or held.placement == "stitched"):
-        torch.cuda.synchronize()
-        held.release()      # a stitched range is per workload; the whole-device arena is shared
     for a in ("state", "plan", "flat", "flats", "raw", "bp", "bm", "bv", "bg", "acc", "device_arena"):
         if hasattr(wl, a):
             setattr(wl, a, None)
     gc.collect()
     torch.cuda.empty_cache()
+
+
+def region_arena(ma):
+    """The whole-device arena and its placement check, or (None, check) when the check fails."""
+    try:
+        arena = hbm.DeviceArena("cuda")
+    except RuntimeError as e:      # e.g. another process holds most of the device
+        log("bench.py: whole-device arena not available (%s)" % e)
+        return None, None
+    _, total = torch.cuda.mem_get_info()
+    if arena.nbytes < 2 * hbm.REGION_BYTES + 16 * hbm.GIB:
+        log("bench.py: the arena (%.0f GiB of %.0f) does not reach the third HBM region; its offsets "
+            "may not map onto the regions as assumed" % (arena.nbytes / hbm.GIB, total / hbm.GIB))
+    verify = arena.verify_regions(ma.probe_two_writes)
+    log("placement check of the whole-device allocation (two write streams, GB/s): same region %s, different "
+        "regions %s -> %s" % (verify["same_GBps"], verify["cross_GBps"], "verified" if verify["verified"] else "NOT verified"))
+    if not verify["verified"]:
+        arena.release()
+        arena = None
+        torch.cuda.empty_cache()
+    return arena, verify
+
+
+def stitched_arena(ma):
+    """The library-built range (ma_arena_create) and its placement check, or (None, None)."""
+    try:
+        st = hbm.StitchedArena(ma.Arena)
+    except ma.MaError as e:
+        log("bench.py: stitched arena not available (%s)" % e)
+        return None, None
+    verify = st.verify_regions(ma.probe_two_writes)
+    verify["blocks_in_place"] = st.in_place
+    log("stitched arena %s; check (two write streams, GB/s): same part %s, different parts %s -> %s"
+        % (st.report, verify["same_GBps"], verify["cross_GBps"], "verified" if verify["verified"] else "NOT verified"))
+    settle()
+    return st, verify
+
+
+def settle():
+    """Waits until the driver has wiped the device's free memory.  Memory that a process gave back
+    (this one or the one before it) is wiped in the background, at 26 GB/s as measured, and while that
+    runs every kernel is about 0.5 % slower (the scan 3 %).  Only free memory can be waiting for its
+    wipe, so free bytes / 20 GB/s bounds the time."""
+    free, _ = torch.cuda.mem_get_info()
+    wait = free / hbm.StitchedArena.WIPE_BYTES_PER_S
+    log("waiting %.1f s: the driver may still be wiping the %.0f GiB of free device memory" % (wait, free / hbm.GIB))
+    time.sleep(wait)
 
 
 # The other workloads a default run reports under "also": (name, timed steps, warm-up steps, rotate).
@@ -502,11 +544,13 @@ def main():
     ap.add_argument("--layout", default="streams", choices=["streams", "tensor"],
                     help="llama3_8b only: how the list's buffers lie in the state: 'streams' = five flat "
                          "buffers p|m|v|g|p_lp (default), 'tensor' = the five buffers of each tensor adjacent")
-    ap.add_argument("--placement", default="region", choices=["region", "stitched", "plain"],
-                    help="'region' (default): cut the state from one whole-device allocation so that its "
-                         "traffic splits evenly over two 96 GiB HBM regions; 'stitched': the same split, but "
-                         "only the state's bytes, mapped by ma_arena_create from physical blocks whose region "
-                         "it finds by timing; 'plain': a fresh allocation")
+    ap.add_argument("--placement", default="stitched", choices=["stitched", "region", "plain"],
+                    help="'stitched' (default): the state lies in a range that ma_arena_create maps from "
+                         "1-GiB physical blocks whose HBM region it finds by timing, so that the traffic of "
+                         "p | m | v | g splits evenly over two 96 GiB regions and the write-only copy lies in "
+                         "the third; 'region': the same split cut from one whole-device allocation, which maps "
+                         "linearly onto the regions on a device whose memory has not been churned (checked; "
+                         "falls back to 'stitched'); 'plain': a fresh allocation")
     ap.add_argument("--rotate", type=int, default=1, metavar="K",
                     help="flat_1e8 / fp16_5e7 / c1 only: step K distinct sub-groups of the workload's shape in "
                          "turn, so that a small sub-group is read from HBM rather than from the caches")
@@ -530,32 +574,19 @@ def main():
     torch.cuda.set_device(0)
     arena, verify = None, None
     if args.placement == "region":
-        try:
-            arena = hbm.DeviceArena("cuda")
-            _, total = torch.cuda.mem_get_info()
-            if arena.nbytes < 2 * hbm.REGION_BYTES + 16 * hbm.GIB:
-                log("bench.py: the arena (%.0f GiB of %.0f) does not reach the third HBM region; its offsets "
-                    "may not map onto the regions as assumed" % (arena.nbytes / hbm.GIB, total / hbm.GIB))
-            verify = arena.verify_regions(ma.probe_two_writes)
-            log("placement check (two write streams, GB/s): same region %s, different regions %s -> %s"
-                % (verify["same_GBps"], verify["cross_GBps"], "verified" if verify["verified"] else "NOT verified"))
-            if not verify["verified"]:
-                # this allocation does not map onto the regions as assumed: let the library find the
-                # regions block by block instead
-                log("bench.py: switching to the stitched placement (ma_arena_create)")
-                arena.release()
-                arena = None
-                torch.cuda.empty_cache()
-                arena = hbm.StitchedArena(ma.Arena)
-        except RuntimeError as e:      # e.g. another process holds most of the device
-            log("bench.py: whole-device arena not available (%s); falling back to a plain allocation" % e)
-            arena = None
-    elif args.placement == "stitched":
-        arena = hbm.StitchedArena(ma.Arena)
+        arena, verify = region_arena(ma)
+        if arena is None:
+            log("bench.py: switching to the stitched placement (ma_arena_create)")
+    if args.placement == "stitched" or (args.placement == "region" and arena is None):
+        arena, verify = stitched_arena(ma)
+        if arena is None:
+            log("bench.py: falling back to a plain allocation")
     t_setup = time.perf_counter()
     wl = Workload(name, ma, args.layout, arena, max(1, args.rotate))
     torch.cuda.synchronize()
     log("setup %.1f s: %s" % (time.perf_counter() - t_setup, wl.desc))
+    if wl.placement == "plain":
+        settle()
 
     ms_per_step = run(wl, args.steps, args.warmup, events_in_region=wl.n >= 10 ** 9)
 
@@ -591,7 +622,7 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": name, "description": wl.desc, "elements": wl.n,
                    "layout": wl.layout, "placement": wl.placement,
-                   "placement_verified": None if verify is None or wl.placement != "region" else verify["verified"],
+                   "placement_verified": None if verify is None or wl.placement == "plain" else verify["verified"],
                    "placement_check": verify,
                    "stitched_arena": wl.device_arena.report if wl.placement == "stitched" else None,
                    "rotating_sets": len(getattr(wl, "flats", None) or [None]),
@@ -631,12 +662,15 @@ def main():
             release(w2)
         out["also"] = also
         if name == "llama3_8b" and arena is not None:
-            # the same list in an ordinary allocation: what a caller sees who cannot place the state
+            # the same list in an ordinary allocation: what a caller sees who does not place the state
+            arena.release()
             arena = None
             import gc
             gc.collect()
             torch.cuda.empty_cache()
             w3 = Workload(name, ma, args.layout, None, 1)
+            torch.cuda.synchronize()
+            settle()
             ms3 = run(w3, 8, 2)
             v3, r3, _ = summarise(w3, ma, ms3, quiet=True)
             roofline["frac_plain"] = r3["frac"]
@@ -646,18 +680,6 @@ def main():
             log("plain placement: %.3f ms/step, update %.0f GB/s (%.1f %%), mix ceiling %s GB/s"
                 % (ms3, r3["achieved"], 100 * r3["frac"], roofline["plain"]["mix_ceiling_GBps"]))
             release(w3)
-            # and in a range of just the state's size that the library stitches from classified blocks
-            st = hbm.StitchedArena(ma.Arena)
-            w4 = Workload(name, ma, args.layout, st, 1)
-            ms4 = run(w4, 8, 2)
-            v4, r4, _ = summarise(w4, ma, ms4, quiet=True)
-            roofline["frac_stitched"] = r4["frac"]
-            roofline["stitched"] = {"placement": w4.placement, "ms_per_step": ms4, "value": v4,
-                                    "achieved": r4["achieved"], "avg_launch_ms": r4["avg_launch_ms"],
-                                    "arena": st.report}
-            log("stitched placement: %.3f ms/step, update %.0f GB/s (%.1f %%), %s"
-                % (ms4, r4["achieved"], 100 * r4["frac"], st.report))
-            release(w4)
         log("extras took %.1f s" % (time.perf_counter() - t_extra))
     print(json.dumps(out), flush=True)
 

@@ -192,12 +192,14 @@ int ma_arena_create(size_t main_bytes, size_t first_region_bytes, size_t side_by
   std::sort(order.begin(), order.end(), [&](size_t a, size_t b) { return count[a] > count[b]; });
   std::vector<std::vector<size_t>> by_region(count.size());
   for (size_t i = 0; i < found.size(); ++i) by_region[size_t(found[i].region)].push_back(i);
+  // blocks of a region are used in the order they were created (on a fresh device: ascending
+  // physical addresses)
+  std::vector<size_t> next_of(count.size(), 0);
   auto take = [&](size_t region, size_t want, std::vector<size_t>& out) {
     auto& v = by_region[region];
     size_t got = 0;
-    while (got < want && !v.empty()) {
-      out.push_back(v.back());
-      v.pop_back();
+    while (got < want && next_of[region] < v.size()) {
+      out.push_back(v[next_of[region]++]);
       ++got;
     }
     return got;
@@ -230,7 +232,12 @@ int ma_arena_create(size_t main_bytes, size_t first_region_bytes, size_t side_by
   a->main_blocks = main_blocks;
   a->side_blocks = side_blocks;
   a->first_blocks = first_blocks;
-  e = hipMemAddressReserve(reinterpret_cast<void**>(&a->base), need * B, 0, nullptr, 0);
+  // aligned to the block size, so that the address translation can use its largest fragments
+  e = hipMemAddressReserve(reinterpret_cast<void**>(&a->base), need * B, B, nullptr, 0);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    e = hipMemAddressReserve(reinterpret_cast<void**>(&a->base), need * B, 0, nullptr, 0);
+  }
   if (e != hipSuccess) {
     release_all();
     delete a;

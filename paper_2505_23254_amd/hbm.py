@@ -5,8 +5,10 @@ Measured on MI355X (two-stream write and mixed read/write probes over a whole-de
 * the HBM behaves as three regions of 96 GiB each.  Streams that lie in ONE region share a lower
   ceiling (two write streams: ~5.7 TB/s inside a region, ~7.1 TB/s across two regions; the 1:1
   read/write mix of the update kernel: ~5.3 TB/s inside one region);
-* one allocation that takes (nearly) all free device memory maps linearly onto the regions: byte
-  offset x of the allocation lies in region x // 96 GiB;
+* one allocation that takes (nearly) all free device memory maps linearly onto the regions (byte
+  offset x of the allocation lies in region x // 96 GiB), but only on a device whose physical memory
+  has not been handed out and taken back in pieces: after a process has created and released
+  virtual-memory blocks, later whole-device allocations (of other processes too) no longer do;
 * the update kernel is fastest when the traffic of the buffers it updates in place (p, m, v, read
   and written) splits evenly over two regions (measured on the 8B-shaped state: 6.4 TB/s with the
   state straddling a region boundary half and half, 5.85-6.0 TB/s with 80 % of it inside one region;
@@ -18,11 +20,12 @@ Measured on MI355X (two-stream write and mixed read/write probes over a whole-de
   the third region: 6.26-6.35 TB/s).  A probe with separate output buffers says the same: what the
   memory system rewards is write traffic spread over more regions than the reads.
 
-Hence this helper: take the device's free memory as one arena and hand out, for a state of a given
-size, the window of the arena whose traffic midpoint sits on a region boundary (DeviceArena).  A
-caller that cannot give the whole device away gets the same placement from StitchedArena: just the
-state's bytes, built by the library's ma_arena_create from physical blocks whose region it finds by
-timing.  Only placement lives here; nothing of the optimizer step.
+Hence two ways to place a state.  StitchedArena (the one bench.py uses) asks the library's
+ma_arena_create for a range built from 1-GiB physical blocks whose region the library finds by
+timing: it works whatever happened on the device before, and holds only what was asked for.
+DeviceArena takes the device's free memory as one allocation and hands out the window whose traffic
+midpoint sits on a region boundary; it needs the linear map, which verify_regions() checks.  Only
+placement lives here; nothing of the optimizer step.
 """
 from typing import Optional, Sequence, Tuple
 
@@ -112,16 +115,7 @@ class DeviceArena:
 
         def rate(pair):
             x, y = (self.buf[o * GIB:o * GIB + nb] for o in pair)
-            two_writes(x, y)
-            best = 0.0
-            for _ in range(reps):
-                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-                a.record()
-                two_writes(x, y)
-                b.record()
-                b.synchronize()
-                best = max(best, 2 * nb / (a.elapsed_time(b) * 1e-3) / 1e9)
-            return best
+            return _pair_rate(two_writes, x, y, reps)
 
         s, c = [rate(p) for p in same], [rate(p) for p in cross]
         return {"verified": bool(min(c) >= margin * max(s)), "same_GBps": [round(x) for x in s],
@@ -147,41 +141,90 @@ class DeviceArena:
 
 
 class StitchedArena:
-    """The placement of DeviceArena without holding the device: every request builds an address range
-    of just the requested size out of 1-GiB physical blocks (`make_arena` = the binding's Arena, i.e.
-    ma_arena_create): the part of `main` before its traffic midpoint from one region, the rest from
-    another, the write-only `side` part from a third.  While it searches it holds at most
-    `max_transient_bytes` (default: all free memory but `reserve_gib`), a fraction of a second; the
-    blocks it does not use go back to the driver.  One request is alive at a time: the next request, or
-    release(), unmaps the previous one (its views must not be used after that)."""
+    """The placement of DeviceArena without holding the device: ONE address range of `2 * half_bytes`
+    (+ `side_bytes`) built by the library's ma_arena_create (`make_arena` = the binding's Arena) out of
+    1-GiB physical blocks whose HBM region it finds by timing: the first half from one region, the
+    second half from another, the side part (for write-only buffers) from a third.  window() and
+    split_window() then cut a state out of it so that its traffic midpoint lies on the boundary
+    between the two halves.  While it searches, the library holds at most `max_transient_bytes`
+    (default: all free memory but `reserve_gib`) for a fraction of a second; the blocks it does not
+    use go back to the driver, which wipes them in the background (measured: ~26 GB/s, during which
+    every kernel runs ~0.5 % slower); `settle_seconds` is how long that takes."""
 
     placement = "stitched"
+    WIPE_BYTES_PER_S = 20e9          # a cautious figure for the driver's background wipe
 
-    def __init__(self, make_arena, max_transient_bytes: Optional[int] = None, reserve_gib: float = 3.0,
-                 block_bytes: int = 0):
-        self.make_arena, self.max_transient, self.reserve = make_arena, max_transient_bytes, reserve_gib
-        self.block_bytes = block_bytes
-        self.current = None
-        self.report = None
-
-    def _build(self, main_bytes, first, side_bytes):
-        self.release()
-        limit = self.max_transient
+    def __init__(self, make_arena, half_bytes: int = 84 * GIB, side_bytes: int = 24 * GIB,
+                 max_transient_bytes: Optional[int] = None, reserve_gib: float = 3.0, block_bytes: int = 0):
+        limit = max_transient_bytes
         if limit is None:
             free, _ = torch.cuda.mem_get_info()
-            limit = max(0, int(free - self.reserve * GIB))
-        self.current = self.make_arena(main_bytes, first, side_bytes, self.block_bytes, limit)
-        self.report = dict(self.current.report)
-        return self.current
+            limit = max(0, int(free - reserve_gib * GIB))
+        self.arena = make_arena(2 * half_bytes, half_bytes, side_bytes, block_bytes, limit)
+        self.report = dict(self.arena.report)
+        self.half = int(self.report["first_region_bytes"])          # whole blocks
+        self.block = block_bytes or GIB
+        released = int(self.report["blocks_created"]) * self.block - int(self.report["main_bytes"]) - int(self.report["side_bytes"])
+        self.settle_seconds = max(0.0, released / self.WIPE_BYTES_PER_S)
+
+    @property
+    def in_place(self) -> bool:
+        """True when every block lies in the region it was wanted in."""
+        r, blk = self.report, self.block
+        return bool(r["first_blocks_in_place"] * blk == r["first_region_bytes"]
+                    and r["second_blocks_in_place"] * blk == r["main_bytes"] - r["first_region_bytes"]
+                    and r["side_blocks_in_place"] * blk == r["side_bytes"])
 
     def window(self, nbytes: int, traffic=None) -> torch.Tensor:
-        return self._build(nbytes, DeviceArena._midpoint(nbytes, traffic), 0).main
+        """A uint8 view of `nbytes` bytes with half of its traffic in each of the two main regions."""
+        cap = self.arena.main.numel()
+        if nbytes > cap:
+            raise ValueError("state of %d bytes does not fit the stitched arena of %d" % (nbytes, cap))
+        start = self.half - DeviceArena._midpoint(nbytes, traffic)
+        start = max(0, min(start, cap - nbytes)) // ALIGN * ALIGN
+        return self.arena.main[start:start + nbytes]
 
     def split_window(self, main_bytes: int, main_traffic, side_bytes: int):
-        a = self._build(main_bytes, DeviceArena._midpoint(main_bytes, main_traffic), side_bytes)
-        return a.main, a.side
+        """window() for the buffers updated in place and the read-only ones, plus `side_bytes` for
+        write-only buffers in the third region."""
+        side = self.arena.side
+        if side is None or side_bytes > side.numel():
+            raise ValueError("side part of %d bytes does not fit the stitched arena" % side_bytes)
+        return self.window(main_bytes, main_traffic), side[:side_bytes]
+
+    def verify_regions(self, two_writes, gib_each: int = 2, reps: int = 3, margin: float = 1.08) -> dict:
+        """An independent check of the finished range, by timing (see DeviceArena.verify_regions):
+        two windows inside one part must be slower together than windows of two different parts.
+        Overwrites the windows; run it before the arena holds data."""
+        nb = gib_each * GIB
+        main, side, half, cap = self.arena.main, self.arena.side, self.half, self.arena.main.numel()
+        if half < 3 * nb or cap - half < 3 * nb:
+            return {"verified": False, "same_GBps": [], "cross_GBps": [], "note": "arena too small to probe"}
+        first = (main[0:nb], main[half - nb:half])
+        second = (main[half:half + nb], main[cap - nb:cap])
+        same, cross = [first, second], [(first[0], second[0]), (first[1], second[1])]
+        if side is not None and side.numel() >= nb:
+            cross += [(first[0], side[:nb]), (second[1], side[side.numel() - nb:])]
+        s = [_pair_rate(two_writes, x, y, reps) for x, y in same]
+        c = [_pair_rate(two_writes, x, y, reps) for x, y in cross]
+        return {"verified": bool(min(c) >= margin * max(s)), "same_GBps": [round(x) for x in s],
+                "cross_GBps": [round(x) for x in c]}
 
     def release(self):
-        if self.current is not None:
-            self.current.close()
-            self.current = None
+        if self.arena is not None:
+            self.arena.close()
+            self.arena = None
+
+
+def _pair_rate(two_writes, x, y, reps: int) -> float:
+    """GB/s of two write streams over the uint8 views x and y (best of `reps` after a warm-up)."""
+    two_writes(x, y)
+    best = 0.0
+    for _ in range(reps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        two_writes(x, y)
+        b.record()
+        b.synchronize()
+        best = max(best, 2 * x.numel() / (a.elapsed_time(b) * 1e-3) / 1e9)
+    return best

@@ -83,38 +83,51 @@ def test_small_states_and_small_arenas():
     assert 0 <= a and b <= c and d <= small.nbytes and c - b < 2 * hbm.ALIGN
 
 
-def test_stitched_arena_requests_the_traffic_midpoint(monkeypatch):
-    """StitchedArena asks the allocator for main cut at its traffic midpoint, keeps one request alive at
-    a time and closes the previous one."""
+def test_stitched_arena_windows_straddle_its_internal_boundary():
+    """StitchedArena asks the allocator once, for two halves and a side part, and cuts every state so
+    that half of its traffic lies on each side of the boundary between the halves."""
     made, closed = [], []
 
     class _Made:
-        def __init__(self, *args):
-            made.append(args)
-            self.report = {"regions_seen": 3}
-            self.main, self.side = _View(0, args[0]), _View(0, args[2]) if args[2] else None
+        def __init__(self, main_bytes, first, side_bytes, block, limit):
+            made.append((main_bytes, first, side_bytes, block, limit))
+            self.report = {"main_bytes": main_bytes, "side_bytes": side_bytes, "first_region_bytes": first,
+                           "blocks_created": 213, "first_blocks_in_place": first // GIB,
+                           "second_blocks_in_place": (main_bytes - first) // GIB,
+                           "side_blocks_in_place": side_bytes // GIB, "regions_seen": 3}
+            self.main, self.side = _View(0, main_bytes), _View(1 << 40, (1 << 40) + side_bytes)
 
         def close(self):
             closed.append(self)
 
-    st = hbm.StitchedArena(_Made, max_transient_bytes=200 * GIB)
+    st = hbm.StitchedArena(_Made, max_transient_bytes=250 * GIB)
+    assert made == [(168 * GIB, 84 * GIB, 24 * GIB, 0, 250 * GIB)]
+    assert st.in_place and st.half == 84 * GIB
+    assert abs(st.settle_seconds - (213 - 192) * GIB / hbm.StitchedArena.WIPE_BYTES_PER_S) < 1e-9
     shapes = synth.llama3_8b_shapes()
     parts, traffic = synth.list_state_parts(shapes), synth.list_traffic(shapes)
     main, side = st.split_window(parts[0], traffic[:4], parts[1])
-    main_bytes, first, side_bytes, block, limit = made[-1]
-    assert (main_bytes, side_bytes, block, limit) == (parts[0], parts[1], 0, 200 * GIB)
-    # half of the traffic of p | m | v | g lies before `first`
+    assert main.numel() == parts[0] and side.numel() == parts[1] and len(made) == 1
+    lo = main.data_ptr() - st.arena.main.data_ptr()
     below = total = 0.0
-    off = 0
+    off = lo
     for nb, w in traffic[:4]:
-        below += w * max(0, min(off + nb, first) - off)
+        below += w * max(0, min(off + nb, st.half) - off)
         total += w * nb
         off += nb
-    assert abs(below / total - 0.5) < 1e-6
-    assert main.numel() == parts[0] and side.numel() == parts[1] and st.report == {"regions_seen": 3}
-    w = st.window(10 * GIB, None)                       # a new request closes the one before
-    assert len(closed) == 1 and made[-1][:3] == (10 * GIB, 5 * GIB, 0) and w.numel() == 10 * GIB
+    assert abs(below / total - 0.5) < 1e-3
+    w = st.window(10 * GIB, None)                       # uniform traffic: centred on the boundary
+    assert w.data_ptr() - st.arena.main.data_ptr() == 79 * GIB and len(made) == 1
+    big = st.window(160 * GIB, [(150 * GIB, 2.0), (10 * GIB, 1.0)])      # clamped into the range
+    assert big.data_ptr() - st.arena.main.data_ptr() + 160 * GIB <= 168 * GIB
+    import pytest
+    with pytest.raises(ValueError):
+        st.window(169 * GIB)
+    with pytest.raises(ValueError):
+        st.split_window(GIB, None, 25 * GIB)
+    st.report["side_blocks_in_place"] = 3               # a part that did not get its region is reported
+    assert not st.in_place
     st.release()
-    assert len(closed) == 2 and st.current is None
+    assert len(closed) == 1 and st.arena is None
     st.release()                                        # idempotent
-    assert len(closed) == 2
+    assert len(closed) == 1

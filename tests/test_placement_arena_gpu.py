@@ -39,10 +39,18 @@ def test_small_arena_is_plain_memory_and_steps_identically():
     # step in ordinary memory
     cfg = synth.config("c1")
     parts, traffic = synth.flat_state_parts(cfg.n, cfg.gdt), synth.flat_traffic(cfg.n, cfg.gdt)
-    st = hbm.StitchedArena(ma.Arena, max_transient_bytes=GIB, block_bytes=block)
+    st = hbm.StitchedArena(ma.Arena, half_bytes=2 * block, side_bytes=block, max_transient_bytes=GIB, block_bytes=block)
+    assert st.half == 2 * block and st.settle_seconds >= 0.0
+    assert st.verify_regions(ma.probe_two_writes)["verified"] is False       # too small to probe, and says so
     main, side = st.split_window(parts[0], traffic[:4], parts[1])
     assert main.numel() == parts[0] and side.numel() == parts[1]
-    assert st.report["first_region_bytes"] in (0, block)             # the midpoint of 14 MB, in whole blocks
+    # the window straddles the boundary between the two halves, half of its traffic on each side
+    lo = main.data_ptr() - st.arena.main.data_ptr()
+    assert lo < st.half < lo + parts[0] and abs((st.half - lo) - hbm.DeviceArena._midpoint(parts[0], traffic[:4])) <= hbm.ALIGN
+    with pytest.raises(ValueError):
+        st.window(5 * block)
+    with pytest.raises(ValueError):
+        st.split_window(parts[0], traffic[:4], 2 * block)
     inside = synth.make_flat(cfg, device="cuda", arena=(main, side))
     plain = synth.make_flat(cfg, device="cuda")
     lo = main.data_ptr()
@@ -58,7 +66,7 @@ def test_small_arena_is_plain_memory_and_steps_identically():
     assert ma.read_result_raw(out, 0) == ma.read_result_raw(out, 1)
     del inside, main, side
     st.release()
-    assert st.current is None
+    assert st.arena is None
 
 
 def test_arena_parts_lie_in_three_regions():
