@@ -52,15 +52,15 @@ ACCUM_SOURCES = ("ma_device.h", "ma_internal.h", "ma_norm.hip", "ma_accum.hip")
 STEP_SHA256 = "89c2b05c0092404313d34a01e6d704e58e6833b33dc7fa1c83da8aa9318592f1"
 ACCUM_SHA256 = "db74af454226034f9c1f11421ec1510a983596dffcaefeabd12dfe2997cc1086"
 MEASURED_TRAFFIC = {      # workload: (bytes per launch, sources, their digest when measured)
-    "llama3_8b": (224846802593, STEP_SOURCES, STEP_SHA256),
-    "flat_1e8": (2800316069, STEP_SOURCES, STEP_SHA256),
-    "fp16_5e7": (1400328248, STEP_SOURCES, STEP_SHA256),
-    "fp32grad_8b": (240908631374, STEP_SOURCES, STEP_SHA256),
-    "auto_fp16_8b": (224846774094, STEP_SOURCES, STEP_SHA256),
-    "qwen14b_4sub": (87972968465, STEP_SOURCES, STEP_SHA256),
-    "bf16_states_8b": (112423623710, STEP_SOURCES, STEP_SHA256),
-    "accumulate_8b": (80301727132, ACCUM_SOURCES, ACCUM_SHA256),
-    "accumulate1_8b": (48181468849, ACCUM_SOURCES, ACCUM_SHA256),
+    "llama3_8b": (224847131614, STEP_SOURCES, STEP_SHA256),
+    "flat_1e8": (2800277378, STEP_SOURCES, STEP_SHA256),
+    "fp16_5e7": (1400285898, STEP_SOURCES, STEP_SHA256),
+    "fp32grad_8b": (240908399879, STEP_SOURCES, STEP_SHA256),
+    "auto_fp16_8b": (224847117850, STEP_SOURCES, STEP_SHA256),
+    "qwen14b_4sub": (87973259267, STEP_SOURCES, STEP_SHA256),
+    "bf16_states_8b": (112423952863, STEP_SOURCES, STEP_SHA256),
+    "accumulate_8b": (80301678360, ACCUM_SOURCES, ACCUM_SHA256),
+    "accumulate1_8b": (48182763199, ACCUM_SOURCES, ACCUM_SHA256),
 }
 
 
