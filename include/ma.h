@@ -458,7 +458,11 @@ int ma_probe_two_writes(void* x, void* y, size_t bytes_each, void* stream);
  *   main_bytes > 0; first_region_bytes <= main_bytes: where main's traffic midpoint lies (rounded to
  *   blocks); side_bytes may be 0; block_bytes: 0 = 1 GiB, else a multiple of 2 MiB >= 64 MiB (smaller
  *   blocks are timed less reliably).  Creation synchronises the device and takes a few
- *   milliseconds per block.  The arena belongs to the device current at creation. */
+ *   milliseconds per block.  The arena belongs to the device current at creation.
+ *   Two things measured on MI355X that a caller should know: the driver wipes the blocks that go
+ *   back in the background (~26 GB/s), and until it is done every kernel on the device runs about
+ *   0.5 % slower; and once blocks have been created and released this way, a later allocation of the
+ *   whole device (in any process) is no longer laid out linearly over the regions. */
 typedef struct ma_arena ma_arena;
 typedef struct ma_arena_report {
   uint64_t main_bytes, side_bytes, first_region_bytes; /* as mapped (whole blocks) */
