@@ -102,3 +102,12 @@ def test_arena_parts_lie_in_three_regions():
     del m, s, first, second
     a.close()
     assert torch.cuda.mem_get_info()[0] >= free - GIB
+    # max_transient_bytes = 0: not one block beyond the arena's own; the parts take whatever regions
+    # come first, the report says which blocks are in place, and the timing never contradicts it
+    from paper_2505_23254_amd import hbm
+    st = hbm.StitchedArena(ma.Arena, half_bytes=6 * GIB, side_bytes=2 * GIB, max_transient_bytes=0)
+    assert st.report["blocks_created"] == 14
+    check = st.verify_regions(ma.probe_two_writes)
+    print("tight arena:", st.report, check)
+    assert check["verified"] or not st.in_place
+    st.release()
