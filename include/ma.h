@@ -476,7 +476,8 @@ int ma_arena_create(size_t main_bytes, size_t first_region_bytes, size_t side_by
 void* ma_arena_main(const ma_arena* arena); /* device address of the main part */
 void* ma_arena_side(const ma_arena* arena); /* device address of the side part, NULL if side_bytes was 0 */
 int ma_arena_get_report(const ma_arena* arena, ma_arena_report* out_host);
-int ma_arena_destroy(ma_arena* arena);      /* unmaps and releases everything; NULL is allowed */
+int ma_arena_destroy(ma_arena* arena);      /* synchronises the device, then unmaps and releases everything (the
+                                               addresses are invalid afterwards); NULL is allowed */
 
 #ifdef __cplusplus
 }

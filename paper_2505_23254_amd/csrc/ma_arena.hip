@@ -288,6 +288,7 @@ int ma_arena_get_report(const ma_arena* arena, ma_arena_report* out_host) {
 int ma_arena_destroy(ma_arena* arena) {
   if (!arena) return MA_OK;
   const size_t bytes = (arena->main_blocks + arena->side_blocks) * arena->block;
+  (void)hipDeviceSynchronize();  // nothing may still be running on memory that is about to be unmapped
   if (arena->base) {
     for (size_t k = 0; k < arena->handles.size(); ++k) (void)hipMemUnmap(arena->base + k * arena->block, arena->block);
     (void)hipMemAddressFree(arena->base, bytes);
