@@ -174,62 +174,55 @@ def _parts_and_traffic(shapes):
 
 def test_llama3_8b_list_every_element():
     """The benchmark workload itself, as the benchmark lays it out and places it (flat streams cut from
-    a whole-device allocation: p | m | v | g across the first region boundary, the copy in the third
-    region): 290 tensors,
+    a range that the library's placement helper maps from physical blocks of known HBM region:
+    p | m | v | g across the boundary between two regions, the copy in a third): 290 tensors,
     8,030,257,152 elements, one scan launch and one gated update launch.  Flag and sum over all
     elements, and EVERY element of p, m, v and the bf16 copy against the oracle: each work item is
     processed exactly once, whichever block draws it."""
-    _need_gib(240)
+    _need_gib(250)
     shapes = synth.llama3_8b_shapes()
     cfg = synth.FlatConfig("llama3_8b", 0, seed=3, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
-    device_arena = hbm.DeviceArena("cuda", reserve_gib=12)      # the checks below need temporaries
-    main, side = device_arena.split_window(*_parts_and_traffic(shapes))
-    ls = synth.make_list(shapes, cfg, device="cuda", layout="streams", arena=(main, side))
-    n = ls.total
-    assert n == 8_030_257_152 and ls.flat.p.numel() == n          # no padding between the views
-    base = device_arena.buf.data_ptr()
-    assert (ls.flat.p.data_ptr() - base) // hbm.REGION_BYTES == 0                     # p starts in the first region,
-    assert (ls.flat.v.data_ptr() + 4 * n - base) // hbm.REGION_BYTES == 1              # v ends in the second,
-    assert (ls.flat.p_lp.data_ptr() - base) // hbm.REGION_BYTES == 2                   # the copy lies in the third
-    # the state before the step is kept in what the allocation has left: three stretches, one piece each
-    used = sorted((t.data_ptr() - base, t.data_ptr() - base + t.numel()) for t in (main, side))
-    free, at = [], 0
-    for a, b in used + [(device_arena.nbytes, device_arena.nbytes)]:
-        free.append([(at + hbm.ALIGN - 1) // hbm.ALIGN * hbm.ALIGN, a])
-        at = b
-    keep = []
-    for _ in range(3):
-        spot = next((f for f in free if f[1] - f[0] >= 4 * n), None)
-        if spot is None:
-            pytest.skip("no room beside the state for a copy of p, m, v")
-        keep.append(device_arena.buf[spot[0]:spot[0] + 4 * n].view(torch.float32))
-        spot[0] += (4 * n + hbm.ALIGN - 1) // hbm.ALIGN * hbm.ALIGN
-    for dst, src in zip(keep, (ls.flat.p, ls.flat.m, ls.flat.v)):
-        dst.copy_(src)
-    full = FullCompare(SLAB, "bf16", "bf16", THREADS)
-    ov_ref, ss_ref = full.norm(ls.flat.g, 1.0)
-    c_ref = oracle.clip_coef(ss_ref, 1.0)
-    assert not ov_ref and 0.005 < c_ref < 0.02         # norm ~ 90
-    plan = ma.MultiPlan(ls.p, ls.m, ls.v, ls.g, ls.p_lp)
-    assert plan.plan.step_chunks >= 65536              # late work items are drawn on demand at this size
-    ws, res = ma.workspace(), ma.new_result()
-    ma.multi_overflow_norm(plan, 1.0, res, ws)
-    ma.multi_adamw_step_gated(plan, _hyper(cfg), 100, 1.0, res, 1.0)
-    ov, ss = ma.read_result(res)
-    assert not ov and abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref
-    assert np.float32(ma.clip_coef(ss, 1.0)) == c_ref
-    assert plan.table[:64].view(torch.int32).cpu().tolist() == [0] * 16
-    full.step(keep, ls.flat.g, (ls.flat.p, ls.flat.m, ls.flat.v, ls.flat.p_lp), oracle_hyper(cfg), 100, 1.0,
-              float(c_ref), "8B list")
-    assert full.elements == n
-    print("8B list: %d elements compared, %d slabs not bit-identical" % (full.elements, full.inexact_slabs))
-    # one NaN in a norm vector: the whole list is skipped, checked over every byte via checksums
-    sums = _checksums_list(ls)
-    ls.g[8].view(torch.int16)[4095] = 0x7FC0
-    ma.multi_overflow_norm(plan, 1.0, res, ws)
-    ma.multi_adamw_step_gated(plan, _hyper(cfg), 101, 1.0, res, 1.0)
-    assert ma.read_result(res)[0] is True
-    assert _checksums_list(ls) == sums
+    # the benchmark's arena, with less room to spare: the copy of the state before the step must fit too
+    arena = hbm.StitchedArena(ma.Arena, half_bytes=64 * hbm.GIB, side_bytes=16 * hbm.GIB)
+    try:
+        print("stitched arena:", arena.report)
+        main, side = arena.split_window(*_parts_and_traffic(shapes))
+        ls = synth.make_list(shapes, cfg, device="cuda", layout="streams", arena=(main, side))
+        n = ls.total
+        assert n == 8_030_257_152 and ls.flat.p.numel() == n          # no padding between the views
+        base = arena.arena.main.data_ptr()
+        assert ls.flat.p.data_ptr() - base < arena.half < ls.flat.m.data_ptr() + 4 * n - base   # the boundary falls into m
+        assert ls.flat.p_lp.data_ptr() == arena.arena.side.data_ptr()                          # the copy lies in the side part
+        keep = [torch.empty(n, dtype=torch.float32, device="cuda") for _ in range(3)]           # the state before the step
+        for dst, src in zip(keep, (ls.flat.p, ls.flat.m, ls.flat.v)):
+            dst.copy_(src)
+        full = FullCompare(SLAB, "bf16", "bf16", THREADS)
+        ov_ref, ss_ref = full.norm(ls.flat.g, 1.0)
+        c_ref = oracle.clip_coef(ss_ref, 1.0)
+        assert not ov_ref and 0.005 < c_ref < 0.02         # norm ~ 90
+        plan = ma.MultiPlan(ls.p, ls.m, ls.v, ls.g, ls.p_lp)
+        assert plan.plan.step_chunks >= 65536              # late work items are drawn on demand at this size
+        ws, res = ma.workspace(), ma.new_result()
+        ma.multi_overflow_norm(plan, 1.0, res, ws)
+        ma.multi_adamw_step_gated(plan, _hyper(cfg), 100, 1.0, res, 1.0)
+        ov, ss = ma.read_result(res)
+        assert not ov and abs(ss - ss_ref) <= SUMSQ_RTOL * ss_ref
+        assert np.float32(ma.clip_coef(ss, 1.0)) == c_ref
+        assert plan.table[:64].view(torch.int32).cpu().tolist() == [0] * 16
+        full.step(keep, ls.flat.g, (ls.flat.p, ls.flat.m, ls.flat.v, ls.flat.p_lp), oracle_hyper(cfg), 100, 1.0,
+                  float(c_ref), "8B list")
+        assert full.elements == n
+        print("8B list: %d elements compared, %d slabs not bit-identical" % (full.elements, full.inexact_slabs))
+        # one NaN in a norm vector: the whole list is skipped, checked over every byte via checksums
+        sums = _checksums_list(ls)
+        ls.g[8].view(torch.int16)[4095] = 0x7FC0
+        ma.multi_overflow_norm(plan, 1.0, res, ws)
+        ma.multi_adamw_step_gated(plan, _hyper(cfg), 101, 1.0, res, 1.0)
+        assert ma.read_result(res)[0] is True
+        assert _checksums_list(ls) == sums
+    finally:                      # the range is unmapped whatever happened; nothing touches its views afterwards
+        torch.cuda.synchronize()
+        arena.release()
 
 
 @pytest.mark.parametrize("layout", ["tensor"])
