@@ -16,7 +16,7 @@ roofline.frac_plain = the same kernel with the state in an ordinary allocation, 
 roofline.mix_ceiling_GBps = what a trivial kernel with the same stream mix reaches on the same buffers.
 
 Workloads: llama3_8b (default; 290-tensor Llama-3-8B-shaped list, 8.03e9 elements, bf16
-gradients, clip 1.0; --layout tensor|streams), flat_1e8, fp16_5e7, c1, c1_onecall (c1 through the whole-step call), qwen14b_4sub (12.57e9 elements as 4 flat
+gradients, clip 1.0; --layout tensor|streams), flat_1e8, fp16_5e7, c1, c1_onecall (c1 through the whole-step call), c1_graph (those calls replayed as one HIP graph), qwen14b_4sub (12.57e9 elements as 4 flat
 sub-groups streamed on one stream); rows beyond the basic step at the 8B element count:
 fp32grad_8b (the 8B list with fp32 gradients: the accumulated flat buffer of Sec. III-C as input,
 4 + 30 B/param), bf16_states_8b (p/m/v held in bf16, truncating stores, 14 B/param), accumulate_8b (4 bf16
@@ -231,8 +231,10 @@ class Workload:
                          "update and loss-scale update without host round trip; layout '%s'" % layout)
         else:
             # c1_onecall: the same sub-group through ma_optimizer_step (two launches instead of three)
-            self.onecall = name == "c1_onecall"
-            cfg = synth.config({"flat_1e8": "c2", "fp16_5e7": "c3a", "c1": "c1", "c1_onecall": "c1"}[name])
+            # c1_graph: those calls for all the rotating sub-groups captured once as a HIP graph; a step
+            # is then one replay
+            self.onecall = name in ("c1_onecall", "c1_graph")
+            cfg = synth.config({"flat_1e8": "c2", "fp16_5e7": "c3a", "c1": "c1", "c1_onecall": "c1", "c1_graph": "c1"}[name])
             self.cfg = cfg
             self.flat = synth.make_flat(cfg, device="cuda",
                                         arena=place_state(synth.flat_state_parts(cfg.n, cfg.gdt),
@@ -248,7 +250,24 @@ class Workload:
             self.kind = "flat"
             if self.onecall:
                 self.kernel_label = "AdamW update that adds up the scan's partials itself (no finalize launch)"
-            self.desc = "flat sub-group n=%d, %s grads, loss_scale %g, max_norm %g%s" % (
+            self.graph = None
+            if name == "c1_graph":
+                h = ma.hyper(cfg.lr, cfg.beta1, cfg.beta2, cfg.eps, cfg.weight_decay, 1)
+                one = lambda f: ma.optimizer_step(f.p, f.m, f.v, f.g, f.p_lp, h, self.t, cfg.loss_scale,
+                                                  cfg.max_norm, self.res, self.ws)
+                one(self.flats[0])                 # the kernels are loaded before the capture
+                torch.cuda.synchronize()
+                self.graph = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(self.graph):
+                    for f in self.flats:
+                        one(f)
+                # one step = one replay = a step of every sub-group (update number fixed at capture; a
+                # training loop keeps it on the device instead: the *_auto calls)
+                self.graph_steps = len(self.flats)
+                self.n = cfg.n * self.graph_steps
+                self.kernel_label = "scan + update launches of %d sub-groups replayed as one HIP graph" % self.graph_steps
+            self.desc = "%sflat sub-group n=%d, %s grads, loss_scale %g, max_norm %g%s" % (
+                "" if self.graph is None else "one HIP graph of %d whole-step calls, one per " % self.graph_steps,
                 cfg.n, cfg.gdt, cfg.loss_scale, cfg.max_norm,
                 "" if rotate == 1 else "; %d distinct sub-groups in rotation (%.0f MB of state)" % (
                     rotate, rotate * synth.flat_state_bytes(cfg.n) / 1e6))
@@ -289,6 +308,10 @@ class Workload:
                 ma.grad_accumulate(self.acc, self.bg, first=False)
             # the last micro-batch of an iteration is accumulated and scanned in one pass
             ma.grad_accumulate_scan(self.acc, self.bg, False, c.loss_scale, self.res, self.ws)
+        elif self.kind == "flat" and self.graph is not None:
+            if record:
+                ev[1].record()
+            self.graph.replay()
         elif self.kind == "flat" and self.onecall:
             f = self.flats[self.t % len(self.flats)]
             if record:      # both launches fall into the second interval
@@ -408,6 +431,8 @@ def summarise(wl, ma, ms_per_step, quiet=False):
         ss = None
     # launches of the dominant kernel in the second phase of a step, and what precedes them
     launches = {"sub": 4, "accum": max(1, wl.micro - 1) if wl.kind == "accum" else 1}.get(wl.kind, 1)
+    if getattr(wl, "graph", None) is not None:
+        launches = wl.graph_steps
     passes = launches if wl.kind == "accum" else 1          # times the second phase sweeps all n elements
     achieved = wl.step_bytes * wl.n * passes / (rest_ms * 1e-3) / 1e9
     gdt_bytes = 4.0 if wl.cfg.gdt == "f32" else 2.0
@@ -434,9 +459,9 @@ def summarise(wl, ma, ms_per_step, quiet=False):
         "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
         "traffic_source": (TRAFFIC_SOURCE.get(wl.name) if traffic is not None else
                            "none: the kernel sources changed since the counters under profiles/ were taken"),
-        "algorithmic_bytes_per_launch": wl.step_bytes * wl.n / (4 if wl.kind == "sub" else 1),
+        "algorithmic_bytes_per_launch": wl.step_bytes * wl.n / (launches if wl.kind in ("sub", "flat") else 1),
         "bytes_per_param": wl.step_bytes,
-        "params_per_launch": wl.n / (4 if wl.kind == "sub" else 1),
+        "params_per_launch": wl.n / (launches if wl.kind in ("sub", "flat") else 1),
         "avg_launch_ms": rest_ms / launches,
         "first_phase": first,
         "whole_step_GBps": whole,
@@ -469,7 +494,7 @@ def mix_ceiling(wl, ma, reps=5):
 
 def release(wl):
     import gc
-    for a in ("state", "plan", "flat", "flats", "raw", "bp", "bm", "bv", "bg", "acc", "device_arena"):
+    for a in ("graph", "state", "plan", "flat", "flats", "raw", "bp", "bm", "bv", "bg", "acc", "device_arena"):
         if hasattr(wl, a):
             setattr(wl, a, None)
     gc.collect()
@@ -524,7 +549,7 @@ def settle():
 
 
 # The other workloads a default run reports under "also": (name, timed steps, warm-up steps, rotate).
-ALSO = (("c1", 400, 40, 32), ("c1_onecall", 400, 40, 32), ("flat_1e8", 100, 10, 1), ("fp16_5e7", 100, 10, 1), ("qwen14b_4sub", 8, 2, 1),
+ALSO = (("c1", 400, 40, 32), ("c1_onecall", 400, 40, 32), ("c1_graph", 40, 5, 32), ("flat_1e8", 100, 10, 1), ("fp16_5e7", 100, 10, 1), ("qwen14b_4sub", 8, 2, 1),
         ("fp32grad_8b", 8, 2, 1), ("auto_fp16_8b", 8, 2, 1), ("bf16_states_8b", 10, 2, 1),
         ("accumulate_8b", 5, 2, 1), ("accumulate1_8b", 8, 2, 1))
 
@@ -535,7 +560,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=None,
-                    choices=["llama3_8b", "fp32grad_8b", "flat_1e8", "fp16_5e7", "c1", "c1_onecall", "qwen14b_4sub",
+                    choices=["llama3_8b", "fp32grad_8b", "flat_1e8", "fp16_5e7", "c1", "c1_onecall", "c1_graph", "qwen14b_4sub",
                              "bf16_states_8b", "accumulate_8b", "accumulate1_8b", "auto_fp16_8b"],
                     help="default: llama3_8b, followed by short runs of all the others (see --also)")
     ap.add_argument("--also", default=None, choices=["all", "none"],
@@ -654,7 +679,10 @@ def main():
                          "unit": "Gparam/s" if w2.kind != "accum" else "G micro-batch elements/s",
                          "roofline": {k: r2[k] for k in ("kernel", "achieved", "frac", "bytes_per_param",
                                                          "avg_launch_ms", "first_phase", "traffic")}})
-            if w2.kind in ("bf16", "sub") or (w2.kind == "flat" and w2.n >= 10 ** 7):
+            if getattr(w2, "graph", None) is not None:
+                also[-1]["sub_group_steps_per_step"] = w2.graph_steps
+                also[-1]["us_per_sub_group_step"] = 1e3 * ms2 / w2.graph_steps
+            if w2.kind in ("bf16", "sub") or (w2.kind == "flat" and w2.n >= 10 ** 7 and getattr(w2, "graph", None) is None):
                 also[-1]["roofline"]["mix_ceiling_GBps"] = mix_ceiling(w2, ma)
             log("also %-15s %9.4f ms/step  %8.2f %s  dominant kernel %.4f ms = %.0f GB/s (%.1f %%)  mix ceiling %s"
                 % (other, ms2, v2, also[-1]["unit"], r2["avg_launch_ms"], r2["achieved"], 100 * r2["frac"],
