@@ -21,8 +21,9 @@ sub-groups streamed on one stream); rows beyond the basic step at the 8B element
 fp32grad_8b (the 8B list with fp32 gradients: the accumulated flat buffer of Sec. III-C as input,
 4 + 30 B/param), bf16_states_8b (p/m/v held in bf16, truncating stores, 14 B/param), accumulate_8b (4 bf16
 micro-batch gradients into the fp32 flat buffer, 6 / 10 B/param), accumulate1_8b (one micro-batch per
-step: the overwrite fused with the scan), auto_fp16_8b (fp16 gradients,
-loss scale, update number and gate all read on the device).
+step: the overwrite fused with the scan), iteration_8b (that pass followed by the gated update reading
+the fp32 buffer: one whole iteration in the order of Sec. IV-A, 6 + 30 B/param), auto_fp16_8b (fp16
+gradients, loss scale, update number and gate all read on the device).
 """
 import argparse
 import json
@@ -212,6 +213,37 @@ class Workload:
                 self.acc = buf[offs[0]:offs[0] + 4 * n].view(torch.float32)
                 self.bg = buf[offs[1]:offs[1] + 2 * n].view(torch.bfloat16)
                 synth._fill_grad(self.bg, cfg.g_std, 1.0, gen)
+        elif name == "iteration_8b":
+            # Sec. IV-A's order: the micro-batch gradient goes into the fp32 flat gradient buffer, the
+            # overflow / norm check is fused into that pass, the gated step reads the buffer (fp32)
+            cfg = synth.FlatConfig(name, 0, seed=3, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
+            cfg.gdt = "f32"
+            self.cfg, self.layout = cfg, "streams"
+            shapes = synth.llama3_8b_shapes()
+            n = sum(k for _, k in shapes)
+            parts, traffic = synth.list_state_parts(shapes, gdt="f32"), synth.list_traffic(shapes, gdt="f32")
+            up = lambda x: (x + synth.ARENA_ALIGN - 1) // synth.ARENA_ALIGN * synth.ARENA_ALIGN
+            where, mb = None, None
+            if self.device_arena is not None:      # the 16-bit micro-batch gradient lies behind the copy
+                try:
+                    main, side = self.device_arena.split_window(parts[0], traffic[:4], up(parts[1]) + 2 * n)
+                    where = (main, side[:parts[1]])
+                    mb = side[up(parts[1]):up(parts[1]) + 2 * n].view(torch.bfloat16)
+                except ValueError as e:
+                    log("bench.py: %s; falling back to a plain allocation" % e)
+                    self.device_arena, self.placement = None, "plain"
+            self.state = synth.make_list(shapes, cfg, device="cuda", layout="streams", arena=where)
+            self.mb = mb if mb is not None else torch.empty(n, dtype=torch.bfloat16, device="cuda")
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(cfg.seed + 1)
+            synth._fill_grad(self.mb, cfg.g_std, 1.0, gen)
+            self.plan = ma.MultiPlan(self.state.p, self.state.m, self.state.v, self.state.g, self.state.p_lp)
+            self.n = self.plan.total
+            assert self.state.flat.g.numel() == self.n
+            self.kind, self.step_bytes = "iter", 30.0
+            self.desc = ("one iteration on the 8B-shaped list: a bf16 micro-batch gradient is written into the "
+                         "fp32 flat gradient buffer with the overflow / norm check fused into that pass, then "
+                         "the gated update reads the buffer as fp32 gradients; placement '%s'" % self.placement)
         elif name == "auto_fp16_8b":
             cfg = synth.FlatConfig(name, 0, seed=7, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0,
                                    gdt="f16", loss_scale=65536.0)
@@ -281,6 +313,11 @@ class Workload:
             ev[0].record()
         if self.kind == "multi":
             ma.multi_overflow_norm(self.plan, c.loss_scale, self.res, self.ws)
+            if record:
+                ev[1].record()
+            ma.multi_adamw_step_gated(self.plan, self.h, self.t, c.loss_scale, self.res, c.max_norm)
+        elif self.kind == "iter":
+            ma.grad_accumulate_scan(self.state.flat.g, self.mb, True, c.loss_scale, self.res, self.ws)
             if record:
                 ev[1].record()
             ma.multi_adamw_step_gated(self.plan, self.h, self.t, c.loss_scale, self.res, c.max_norm)
@@ -440,6 +477,11 @@ def summarise(wl, ma, ms_per_step, quiet=False):
         first = None
         value = wl.n / (ms_per_step * 1e-3) / 1e9
         whole = 6.0 * wl.n / (ms_per_step * 1e-3) / 1e9
+    elif wl.kind == "iter":
+        first = {"kernel": "micro-batch gradient into the fp32 flat buffer, fused with the overflow / norm check",
+                 "avg_ms": first_ms, "bytes_per_param": 6.0, "achieved": 6.0 * wl.n / (first_ms * 1e-3) / 1e9}
+        value = wl.n / (ms_per_step * 1e-3) / 1e9
+        whole = (6.0 + wl.step_bytes) * wl.n / (ms_per_step * 1e-3) / 1e9
     elif wl.kind == "accum":
         first = {"kernel": "first micro-batch (overwrite)", "avg_ms": first_ms, "bytes_per_param": 6.0,
                  "achieved": 6.0 * wl.n / (first_ms * 1e-3) / 1e9}
@@ -458,6 +500,7 @@ def summarise(wl, ma, ms_per_step, quiet=False):
         "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
         "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
         "traffic_source": (TRAFFIC_SOURCE.get(wl.name) if traffic is not None else
+                           "none: no counter run for this workload" if wl.name not in MEASURED_TRAFFIC else
                            "none: the kernel sources changed since the counters under profiles/ were taken"),
         "algorithmic_bytes_per_launch": wl.step_bytes * wl.n / (launches if wl.kind in ("sub", "flat") else 1),
         "bytes_per_param": wl.step_bytes,
@@ -494,7 +537,7 @@ def mix_ceiling(wl, ma, reps=5):
 
 def release(wl):
     import gc
-    for a in ("graph", "state", "plan", "flat", "flats", "raw", "bp", "bm", "bv", "bg", "acc", "device_arena"):
+    for a in ("graph", "state", "plan", "flat", "flats", "raw", "bp", "bm", "bv", "bg", "acc", "mb", "device_arena"):
         if hasattr(wl, a):
             setattr(wl, a, None)
     gc.collect()
@@ -525,7 +568,7 @@ def region_arena(ma):
 def stitched_arena(ma):
     """The library-built range (ma_arena_create) and its placement check, or (None, None)."""
     try:
-        st = hbm.StitchedArena(ma.Arena)
+        st = hbm.StitchedArena(ma.Arena, side_bytes=32 * hbm.GIB)      # the largest side part: iteration_8b's 30 GiB
     except ma.MaError as e:
         log("bench.py: stitched arena not available (%s)" % e)
         return None, None
@@ -550,7 +593,7 @@ def settle():
 
 # The other workloads a default run reports under "also": (name, timed steps, warm-up steps, rotate).
 ALSO = (("c1", 400, 40, 32), ("c1_onecall", 400, 40, 32), ("c1_graph", 40, 5, 32), ("flat_1e8", 100, 10, 1), ("fp16_5e7", 100, 10, 1), ("qwen14b_4sub", 8, 2, 1),
-        ("fp32grad_8b", 8, 2, 1), ("auto_fp16_8b", 8, 2, 1), ("bf16_states_8b", 10, 2, 1),
+        ("fp32grad_8b", 8, 2, 1), ("iteration_8b", 8, 2, 1), ("auto_fp16_8b", 8, 2, 1), ("bf16_states_8b", 10, 2, 1),
         ("accumulate_8b", 5, 2, 1), ("accumulate1_8b", 8, 2, 1))
 
 
@@ -561,7 +604,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=None,
                     choices=["llama3_8b", "fp32grad_8b", "flat_1e8", "fp16_5e7", "c1", "c1_onecall", "c1_graph", "qwen14b_4sub",
-                             "bf16_states_8b", "accumulate_8b", "accumulate1_8b", "auto_fp16_8b"],
+                             "bf16_states_8b", "accumulate_8b", "accumulate1_8b", "auto_fp16_8b", "iteration_8b"],
                     help="default: llama3_8b, followed by short runs of all the others (see --also)")
     ap.add_argument("--also", default=None, choices=["all", "none"],
                     help="after the timed region also run the other workloads, the plain-placement run and "

@@ -694,3 +694,49 @@ def test_randomised_bf16_states_and_accumulation():
         ov_ref, ss_ref = oracle.overflow_norm(ref, "f32", S)
         ov, ss = ma.read_result(res)
         assert ov == ov_ref is False and abs(ss - ss_ref) <= 1e-11 * max(ss_ref, 1e-300), what
+
+
+def test_whole_iteration_accumulate_check_step():
+    """The order of Sec. IV-A at list scale: micro-batch gradients accumulate into the fp32 flat gradient
+    buffer, the fused check runs inside the last accumulation pass (no separate scan), and the gated
+    multi-tensor step takes that buffer as its fp32 gradient.  Three iterations: one micro-batch; three
+    with an infinity in the second (the step is skipped, the state stays as it is, the update number
+    does not advance); two, clean again.  Every element against the oracle's chain of the same calls."""
+    shapes = [("a", 64 * 1000), ("b", 4096 * 37), ("c", 64), ("d", 128 * 4097), ("e", 64 * 333)]
+    cfg = synth.FlatConfig("iteration", 0, seed=11, m_std=1e-4, v_std=1e-8, step=7, max_norm=1.0, gdt="f32")
+    ls = synth.make_list(shapes, cfg, device="cuda", layout="streams")
+    n = ls.total
+    assert ls.flat.g.numel() == n and ls.flat.g.dtype == torch.float32       # one flat buffer, no padding
+    plan = ma.MultiPlan(ls.p, ls.m, ls.v, ls.g, ls.p_lp)
+    ws, res = ma.workspace(), ma.new_result()
+    ref = _host_state(ls.flat)
+    acc_ref = np.full(n, np.nan, np.float32)
+    S, t = 256.0, cfg.step
+    for it, (micro, poison) in enumerate([(1, False), (3, True), (2, False)]):
+        for k in range(micro):
+            g = _micro_grad(n, 5000 + 10 * it + k, "bf16", S)
+            if poison and k == 1:
+                g.view(torch.int16)[n - 12345] = 0x7F80                      # +inf in one micro-batch
+            oracle.grad_accumulate(acc_ref, host_grad(g), "bf16", first=(k == 0))
+            if k < micro - 1:
+                ma.grad_accumulate(ls.flat.g, g, first=(k == 0))
+            else:
+                ma.grad_accumulate_scan(ls.flat.g, g, k == 0, S, res, ws)
+        ma.multi_adamw_step_gated(plan, _hyper(cfg), t, S, res, cfg.max_norm)
+        ov_ref, ss_ref = oracle.overflow_norm(acc_ref, "f32", S)
+        ov, ss = ma.read_result(res)
+        what = "iteration %d (%d micro-batches)" % (it, micro)
+        assert ov == ov_ref == poison, what
+        assert np.array_equal(host_f32(ls.flat.g).view(np.uint32), acc_ref.view(np.uint32)), what
+        if not poison:
+            assert abs(ss - ss_ref) <= 1e-11 * ss_ref, what
+            c_ref = oracle.clip_coef(ss_ref, float(np.float32(cfg.max_norm)))
+            assert np.float32(ma.clip_coef(ss, cfg.max_norm)) == c_ref
+            ref["lp"] = oracle.adamw_step(ref["p"], ref["m"], ref["v"], acc_ref, "f32", "bf16", oracle_hyper(cfg),
+                                          t, S, float(c_ref))
+            t += 1
+        got = _host_state(ls.flat)
+        assert_state_close(got, ref, what)
+        for k in ("p", "m", "v"):                                            # in fact bit for bit
+            assert np.array_equal(got[k].view(np.uint32), ref[k].view(np.uint32)), what + " " + k
+    assert t == cfg.step + 2
