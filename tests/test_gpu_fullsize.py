@@ -279,7 +279,20 @@ def test_14b_class_four_sub_groups():
     shapes = synth.qwen14b_class_shapes()
     total = sum(n for _, n in shapes)
     cfg = synth.FlatConfig("qwen14b_4sub", 0, seed=4, m_std=1e-4, v_std=1e-8, step=100, max_norm=1.0)
-    fl = synth.make_flat(cfg, device="cuda", n=total)
+    # placed as the benchmark places it: in the library-built arena, p | m | v | g around the boundary
+    # between two HBM regions, the copy in a third
+    arena = hbm.StitchedArena(ma.Arena)
+    try:
+        print("stitched arena:", arena.report)
+        where = arena.split_window(synth.flat_state_parts(total)[0], synth.flat_traffic(total)[:4],
+                                   synth.flat_state_parts(total)[1])
+        _four_sub_groups(synth.make_flat(cfg, device="cuda", n=total, arena=where), shapes, total, cfg)
+    finally:                      # the range is unmapped whatever happened; nothing touches its views afterwards
+        torch.cuda.synchronize()
+        arena.release()
+
+
+def _four_sub_groups(fl, shapes, total, cfg):
     sub = total // 4
     assert sub == 3_141_898_240
     ranges = _list_ranges(shapes, total, 19, 600)
