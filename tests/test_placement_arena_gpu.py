@@ -35,6 +35,12 @@ def test_small_arena_is_plain_memory_and_steps_identically():
     assert free1 >= free0 - 7 * block                # (kernels and events of a first use: some tens of MB)
     ma.Arena(6 * block, 2 * block, block, block_bytes=block, max_transient_bytes=GIB).close()
     assert torch.cuda.mem_get_info()[0] >= free1 - 8 * MIB
+    # no side part, everything in the second part: the degenerate request is served too
+    b = ma.Arena(2 * block, 0, 0, block_bytes=block, max_transient_bytes=0)
+    assert b.side is None and b.report["first_region_bytes"] == 0 and b.report["blocks_created"] == 2
+    b.main.fill_(3)
+    assert int(b.main[-1]) == 3
+    b.close()
     # one step of a flat sub-group placed through the placement interface: bit-identical to the same
     # step in ordinary memory
     cfg = synth.config("c1")
