@@ -380,6 +380,60 @@ def test_sub_group_streaming_miniature():
     assert_state_close(got, ref, "sub-groups")
 
 
+def test_parameter_groups_share_one_global_norm():
+    """Two parameter groups of one model, as fine-tuning recipes have them: the matrices with weight
+    decay, the norm vectors without and at another learning rate.  Each group is a prepared list of
+    its own; their scans are combined into ONE global norm (the clip coefficient is a property of the
+    whole gradient), and each group's gated step reads that result with its own hyper-parameters.  An
+    overflow in the small group skips both."""
+    shapes = synth.scaled_shapes(synth.llama3_8b_shapes(), 2048, ragged=True)
+    cfg = synth.FlatConfig("groups", 0, seed=81, m_std=1e-4, v_std=1e-8, step=42, max_norm=0.05)
+    ls = synth.make_list(shapes, cfg, device="cuda")
+    small = [i for i, (name, _) in enumerate(shapes) if "norm" in name]  # the norm vectors
+    large = [i for i in range(len(shapes)) if i not in small]
+    assert small and large
+    pick = lambda lst, idx: [lst[i] for i in idx]
+    hy = {"large": dict(lr=1e-5, wd=0.01), "small": dict(lr=3e-5, wd=0.0)}
+    groups = {"large": large, "small": small}
+    plans = {k: ma.MultiPlan(*(pick(x, idx) for x in (ls.p, ls.m, ls.v, ls.g, ls.p_lp))) for k, idx in groups.items()}
+    refs = {i: dict(p=host_f32(ls.p[i]), m=host_f32(ls.m[i]), v=host_f32(ls.v[i]), lp=synth.bits16(ls.p_lp[i]),
+                    pdt="bf16") for i in range(len(shapes))}
+    # oracle: per-group sums in list order, added in group order; one clip coefficient for all
+    ss_groups = [sum(oracle.overflow_norm(host_grad(ls.g[i]), "bf16")[1] for i in groups[k]) for k in ("large", "small")]
+    ss_ref = ss_groups[0] + ss_groups[1]
+    c_ref = oracle.clip_coef(ss_ref, float(np.float32(cfg.max_norm)))
+    assert c_ref < 1
+    for k, idx in groups.items():
+        h = oracle.hyper(hy[k]["lr"], cfg.beta1, cfg.beta2, cfg.eps, hy[k]["wd"], 1)
+        for i in idx:
+            r = refs[i]
+            r["lp"] = oracle.adamw_step(r["p"], r["m"], r["v"], host_grad(ls.g[i]), "bf16", "bf16", h, 42, 1.0, float(c_ref))
+    ws, parts, res = ma.workspace(), ma.new_result(2), ma.new_result()
+    for j, k in enumerate(("large", "small")):
+        ma.multi_overflow_norm(plans[k], 1.0, parts, ws, index=j)
+    ma.norm_combine(parts, 2, res)
+    for k in ("large", "small"):
+        ma.multi_adamw_step_gated(plans[k], ma.hyper(hy[k]["lr"], cfg.beta1, cfg.beta2, cfg.eps, hy[k]["wd"], 1),
+                                  42, 1.0, res, cfg.max_norm)
+    ov, ss = ma.read_result(res)
+    assert not ov and abs(ss - ss_ref) <= 1e-12 * ss_ref
+    assert np.float32(ma.clip_coef(ss, cfg.max_norm)) == c_ref
+    for i in range(len(shapes)):
+        got = dict(p=host_f32(ls.p[i]), m=host_f32(ls.m[i]), v=host_f32(ls.v[i]), lp=synth.bits16(ls.p_lp[i]))
+        assert_state_close(got, refs[i], "tensor %d (%s)" % (i, shapes[i][0]))
+    # an overflow in one norm vector: the combined result gates BOTH groups
+    ls.g[small[0]].view(torch.int16)[0] = 0x7F81                         # a NaN pattern of bf16
+    before = ls.flat.arena.cpu().numpy().tobytes()
+    for j, k in enumerate(("large", "small")):
+        ma.multi_overflow_norm(plans[k], 1.0, parts, ws, index=j)
+    ma.norm_combine(parts, 2, res)
+    for k in ("large", "small"):
+        ma.multi_adamw_step_gated(plans[k], ma.hyper(hy[k]["lr"], cfg.beta1, cfg.beta2, cfg.eps, hy[k]["wd"], 1),
+                                  43, 1.0, res, cfg.max_norm)
+    assert ma.read_result(res)[0] is True
+    assert ls.flat.arena.cpu().numpy().tobytes() == before
+
+
 def test_several_steps_track_the_oracle():
     """Ten consecutive steps with fresh gradients: the two trajectories stay within the bar at
     every step (they are bit-identical as long as the clip coefficients agree)."""
