@@ -486,6 +486,61 @@ def test_two_sub_groups_on_two_streams():
         assert_state_close(_host_state(st, "bf16"), refs[k], "stream %d" % k)
 
 
+def test_four_host_threads_on_four_streams():
+    """The entry points may be called from several host threads at once (the error message is per
+    thread, the per-device caches are guarded): four threads, each with its own sub-group, stream,
+    workspace and result slot, run 20 iterations of scan + gated step concurrently, one of them through
+    the whole-step call and one through a prepared list; every sub-group ends where the oracle puts it."""
+    import threading
+    sizes = (300_007, 1_000_003, 65_536, 2_000_001)
+    cfgs = [synth.FlatConfig("t%d" % k, n, seed=160 + k, gdt=("bf16", "f16", "bf16", "f16")[k], m_std=1e-4,
+                             v_std=1e-8, step=3, loss_scale=(1.0, 256.0, 1.0, 1024.0)[k], max_norm=(0.02, 0.5, 0.0, 0.1)[k])
+            for k, n in enumerate(sizes)]
+    sts = [synth.make_flat(c, device="cuda") for c in cfgs]
+    refs = [_host_state(st, "bf16") for st in sts]
+    iters = 20
+    for k, c in enumerate(cfgs):
+        g = host_grad(sts[k].g)
+        for it in range(iters):
+            ov, _, _ = oracle.optimizer_step(refs[k]["p"], refs[k]["m"], refs[k]["v"], g, c.gdt, refs[k]["lp"], "bf16",
+                                             oracle_hyper(c), 3 + it, c.loss_scale, c.max_norm)
+            assert not ov
+    plan = ma.MultiPlan([sts[3].p], [sts[3].m], [sts[3].v], [sts[3].g], [sts[3].p_lp])
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream() for _ in sizes]
+    wss = [ma.workspace() for _ in sizes]
+    ress = [ma.new_result() for _ in sizes]
+    errors, start = [], threading.Barrier(len(sizes))
+
+    def work(k):
+        try:
+            c, st = cfgs[k], sts[k]
+            start.wait()
+            for it in range(iters):
+                if k == 2:
+                    ma.optimizer_step(st.p, st.m, st.v, st.g, st.p_lp, _hyper(c), 3 + it, c.loss_scale, c.max_norm,
+                                      ress[k], wss[k], stream=streams[k])
+                elif k == 3:
+                    ma.multi_overflow_norm(plan, c.loss_scale, ress[k], wss[k], stream=streams[k])
+                    ma.multi_adamw_step_gated(plan, _hyper(c), 3 + it, c.loss_scale, ress[k], c.max_norm, stream=streams[k])
+                else:
+                    ma.overflow_norm(st.g, c.loss_scale, ress[k], wss[k], stream=streams[k])
+                    ma.adamw_step_gated(st.p, st.m, st.v, st.g, st.p_lp, _hyper(c), 3 + it, c.loss_scale, ress[k],
+                                        c.max_norm, stream=streams[k])
+        except Exception as e:      # noqa: BLE001 - reported by the main thread
+            errors.append((k, repr(e)))
+
+    threads = [threading.Thread(target=work, args=(k,)) for k in range(len(sizes))]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for k, st in enumerate(sts):
+        assert_state_close(_host_state(st, "bf16"), refs[k], "thread %d" % k)
+
+
 def test_multi_list_repeated_launches():
     """A 1/512-scale 8B-shaped list (about 4000 work items), four iterations on one plan, the third
     one skipped by an overflow: every element is updated exactly once per applied iteration and the
