@@ -41,5 +41,21 @@ def build(force: bool = True, extra_flags=(), out: str = OUT) -> str:
     return out
 
 
+EXAMPLE_SRC = os.path.join(HERE, "..", "examples", "step_from_c.c")
+EXAMPLE_OUT = os.path.join(HERE, "step_from_c")
+
+
+def build_example(out: str = EXAMPLE_OUT) -> str:
+    """The plain-C99 example program (examples/step_from_c.c), linked against the library."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c99", "-O1", "-Wall", "-Wextra", "-Werror", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(HERE, "..", "include"), "-I", os.path.join(rocm, "include"), EXAMPLE_SRC,
+           "-L", HERE, "-lma_step", "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", out]
+    subprocess.run(cmd, check=True)
+    return out
+
+
 if __name__ == "__main__":
     print(build(force=True, extra_flags=sys.argv[1:]))
+    print(build_example())
