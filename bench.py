@@ -12,7 +12,8 @@ bounded sample of the same workload.
 
 With no --workload the line describes the 8B-shaped list (K timed steps) and carries, measured in the
 same process after the timed region: "also" = the other workloads below (their own short runs),
-roofline.frac_plain = the same kernel with the state in an ordinary allocation, and
+roofline.frac_plain = the same kernel with the state in an ordinary allocation,
+check_fp32_by_model = the fused overflow / norm check alone over fp32 flat gradient buffers of four model sizes, and
 roofline.mix_ceiling_GBps = what a trivial kernel with the same stream mix reaches on the same buffers.
 
 Workloads: llama3_8b (default; 290-tensor Llama-3-8B-shaped list, 8.03e9 elements, bf16
@@ -580,6 +581,43 @@ def stitched_arena(ma):
     return st, verify
 
 
+# Sec. VI-B reports the fused overflow check per model size, on the fp32 flat gradient buffer.  The same
+# here: the check (fp32 mask of Algorithm 1, fused with the sum of squares) over fp32 buffers with the
+# element counts of four decoder shapes of the sizes the paper evaluates (embedding, per layer q / k /
+# v / o, gate / up / down, two norm vectors, LM head; no biases).
+CHECK_SHAPES = (("7B-class", (3584, 18944, 28, 4, 128, 152064)), ("8B-class", (4096, 14336, 32, 8, 128, 128256)),
+                ("14B-class", (5120, 13824, 48, 8, 128, 152064)), ("32B-class", (5120, 27648, 64, 8, 128, 152064)))
+
+
+def check_by_model(ma, arena, reps=5):
+    ws, res = ma.workspace(), ma.new_result()
+    rows = []
+    for label, dims in CHECK_SHAPES:
+        n = sum(k for _, k in synth.decoder_shapes(*dims))
+        try:
+            g = arena.window(4 * n, None).view(torch.float32)
+        except ValueError:
+            continue
+        for a in range(0, n, 1 << 30):
+            g[a:a + (1 << 30)].fill_(1e-3)
+        ma.overflow_norm(g, 1.0, res, ws)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        ev[0].record()
+        for k in range(reps):
+            ma.overflow_norm(g, 1.0, res, ws)
+            ev[k + 1].record()
+        torch.cuda.synchronize()
+        ms = ev[0].elapsed_time(ev[reps]) / reps
+        ov, ss = ma.read_result(res)
+        if ov or abs(ss - 1e-6 * n) > 1e-6 * (1e-6 * n):
+            sys.exit("bench.py: the check over the %s buffer returned overflow=%s, sumsq=%r" % (label, ov, ss))
+        rows.append({"shape": label, "elements": n, "buffer_GiB": 4 * n / hbm.GIB, "ms": ms,
+                     "GBps": 4.0 * n / (ms * 1e-3) / 1e9, "frac": 4.0 * n / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS})
+        log("fused check, fp32 flat gradient buffer, %-9s %14d elements (%6.2f GiB): %7.3f ms  %.0f GB/s (%.1f %%)"
+            % (label, n, 4 * n / hbm.GIB, ms, rows[-1]["GBps"], 100 * rows[-1]["frac"]))
+    return rows
+
+
 def settle():
     """Waits until the driver has wiped the device's free memory.  Memory that a process gave back
     (this one or the one before it) is wiped in the background, at 26 GB/s as measured, and while that
@@ -732,6 +770,8 @@ def main():
                    also[-1]["roofline"].get("mix_ceiling_GBps")))
             release(w2)
         out["also"] = also
+        if arena is not None:
+            out["check_fp32_by_model"] = check_by_model(ma, arena)
         if name == "llama3_8b" and arena is not None:
             # the same list in an ordinary allocation: what a caller sees who does not place the state
             arena.release()
