@@ -17,7 +17,8 @@ check_fp32_by_model = the fused overflow / norm check alone over fp32 flat gradi
 roofline.mix_ceiling_GBps = what a trivial kernel with the same stream mix reaches on the same buffers.
 
 Workloads: llama3_8b (default; 290-tensor Llama-3-8B-shaped list, 8.03e9 elements, bf16
-gradients, clip 1.0; --layout tensor|streams), flat_1e8, fp16_5e7, c1, c1_onecall (c1 through the whole-step call), c1_graph (those calls replayed as one HIP graph), qwen14b_4sub (12.57e9 elements as 4 flat
+gradients, clip 1.0; --layout tensor|streams), flat_1e8, fp16_5e7, share8_8b (a flat slice of 1/8 of the 8B list: one data-parallel rank's share over eight GPUs),
+c1, c1_onecall (c1 through the whole-step call), c1_graph (those calls replayed as one HIP graph), qwen14b_4sub (12.57e9 elements as 4 flat
 sub-groups streamed on one stream); rows beyond the basic step at the 8B element count:
 fp32grad_8b (the 8B list with fp32 gradients: the accumulated flat buffer of Sec. III-C as input,
 4 + 30 B/param), bf16_states_8b (p/m/v held in bf16, truncating stores, 14 B/param), accumulate_8b (4 bf16
@@ -267,7 +268,11 @@ class Workload:
             # c1_graph: those calls for all the rotating sub-groups captured once as a HIP graph; a step
             # is then one replay
             self.onecall = name in ("c1_onecall", "c1_graph")
-            cfg = synth.config({"flat_1e8": "c2", "fp16_5e7": "c3a", "c1": "c1", "c1_onecall": "c1", "c1_graph": "c1"}[name])
+            if name == "share8_8b":      # one data-parallel rank's share of the 8B list over eight GPUs, as a flat slice
+                cfg = synth.FlatConfig(name, sum(k for _, k in synth.llama3_8b_shapes()) // 8, seed=9, m_std=1e-4,
+                                       v_std=1e-8, step=100, max_norm=1.0)
+            else:
+                cfg = synth.config({"flat_1e8": "c2", "fp16_5e7": "c3a", "c1": "c1", "c1_onecall": "c1", "c1_graph": "c1"}[name])
             self.cfg = cfg
             self.flat = synth.make_flat(cfg, device="cuda",
                                         arena=place_state(synth.flat_state_parts(cfg.n, cfg.gdt),
@@ -630,7 +635,7 @@ def settle():
 
 
 # The other workloads a default run reports under "also": (name, timed steps, warm-up steps, rotate).
-ALSO = (("c1", 400, 40, 32), ("c1_onecall", 400, 40, 32), ("c1_graph", 40, 5, 32), ("flat_1e8", 100, 10, 1), ("fp16_5e7", 100, 10, 1), ("qwen14b_4sub", 8, 2, 1),
+ALSO = (("c1", 400, 40, 32), ("c1_onecall", 400, 40, 32), ("c1_graph", 40, 5, 32), ("flat_1e8", 100, 10, 1), ("fp16_5e7", 100, 10, 1), ("share8_8b", 20, 4, 1), ("qwen14b_4sub", 8, 2, 1),
         ("fp32grad_8b", 8, 2, 1), ("iteration_8b", 8, 2, 1), ("auto_fp16_8b", 8, 2, 1), ("bf16_states_8b", 10, 2, 1),
         ("accumulate_8b", 5, 2, 1), ("accumulate1_8b", 8, 2, 1))
 
@@ -641,7 +646,7 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default=None,
-                    choices=["llama3_8b", "fp32grad_8b", "flat_1e8", "fp16_5e7", "c1", "c1_onecall", "c1_graph", "qwen14b_4sub",
+                    choices=["llama3_8b", "fp32grad_8b", "flat_1e8", "fp16_5e7", "share8_8b", "c1", "c1_onecall", "c1_graph", "qwen14b_4sub",
                              "bf16_states_8b", "accumulate_8b", "accumulate1_8b", "auto_fp16_8b", "iteration_8b"],
                     help="default: llama3_8b, followed by short runs of all the others (see --also)")
     ap.add_argument("--also", default=None, choices=["all", "none"],
