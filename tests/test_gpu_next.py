@@ -281,6 +281,47 @@ def test_auto_iterations_track_the_oracle(gdt):
     assert state_ref.skipped == 3 and state_ref.step == 41 + 9
 
 
+def test_auto_long_trajectory_without_host_round_trips():
+    """300 iterations enqueued back to back with no synchronisation in between: scale, update number and
+    gate live on the device the whole time.  Overflows are planted at fixed iterations, so the oracle's
+    trajectory (run first) tells which scale each iteration's gradient carries; at the end the state,
+    the scale, the counters and the last result equal the oracle's.  The scale grows (window 4) until
+    the fp16 gradients overflow by themselves, falls, and grows again, many times."""
+    n, iters = 20_011, 300
+    S0 = 4096.0
+    cfg = synth.FlatConfig("t", n, seed=131, gdt="f16", m_std=1e-4, v_std=1e-8, max_norm=0.05)
+    st = synth.make_flat(cfg, device="cuda")
+    ref = _host_state(st)
+    h_ref, h = oracle_hyper(cfg), _hyper(cfg)
+    state_ref, cfg_ref = oracle.scaler_state(scale=S0, step=0), oracle.scaler_cfg(window=4)
+    bad = {it for it in range(iters) if it % 23 == 5 or it % 57 == 11}
+    base = _micro_grad(n, 977, "f16", 1.0).to(torch.float32)                  # one direction, re-scaled per iteration
+    grads, last = [], None
+    for it in range(iters):
+        g = (base * (state_ref.scale * (1.0 + 0.01 * (it % 7)))).to(torch.float16)
+        if it in bad:
+            g.view(torch.int16)[(it * 7919) % n] = 0x7C00                        # +inf
+        grads.append(g)
+        last = oracle.optimizer_step_auto(ref["p"], ref["m"], ref["v"], host_grad(g), "f16", ref["lp"], "bf16",
+                                          h_ref, state_ref, cfg_ref, cfg.max_norm)
+    # besides the planted ones the growing scale runs into the fp16 range on its own, as in training
+    assert state_ref.skipped > len(bad) and state_ref.step == iters - state_ref.skipped and state_ref.step > 200
+    scaler, scfg = ma.new_scaler(S0, 0), ma.scaler_config(window=4)
+    ws, res = ma.workspace(), ma.new_result()
+    torch.cuda.synchronize()
+    for it in range(iters):                                                     # nothing below waits for the device
+        ma.overflow_norm_auto(grads[it], scaler, res, ws)
+        ma.adamw_step_auto(st.p, st.m, st.v, grads[it], st.p_lp, h, scaler, res, cfg.max_norm)
+        ma.scaler_update(scaler, res, scfg)
+    ov, ss = ma.read_result(res)
+    assert ov == last[0] and (ov or abs(ss - last[1]) <= 1e-12 * last[1])
+    assert ma.read_scaler(scaler) == (state_ref.scale, state_ref.good_steps, state_ref.step, state_ref.skipped)
+    got = _host_state(st)
+    assert_state_close(got, ref, "after %d iterations" % iters)
+    for k in ("p", "m", "v"):
+        assert np.array_equal(got[k].view(np.uint32), ref[k].view(np.uint32)), k
+
+
 def test_auto_equals_host_driven_gated_step():
     """The device-evaluated bias corrections equal the host's: an auto step is bit-identical to the
     gated step given the same scale and update number, at small and large update numbers."""
