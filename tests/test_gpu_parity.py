@@ -632,6 +632,52 @@ def test_randomised_sizes_alignments_and_hyper_parameters():
         assert np.array_equal(got["lp"], ref["lp"]), what
 
 
+def test_list_of_twenty_thousand_tiny_tensors():
+    """Many small tensors (0 to 300 elements each, packed back to back, so nearly every one starts off
+    the packet grid): one work item per tensor, a table of 20,000 rows searched on the scalar unit.
+    Since the tensors tile the flat buffers without gaps the oracle runs once over the flat state."""
+    rng = np.random.default_rng(777)
+    sizes = rng.integers(0, 301, 20_000).tolist()
+    sizes[17] = 5000                                                  # and one that spans two work items
+    shapes = [("t%d" % i, int(k)) for i, k in enumerate(sizes)]
+    cfg = synth.FlatConfig("tiny", 0, seed=91, m_std=1e-4, v_std=1e-8, step=12, max_norm=0.05, gdt="f16",
+                           loss_scale=64.0)
+    ls = synth.make_list(shapes, cfg, device="cuda", align_elems=1)
+    fl = ls.flat
+    total = sum(sizes)
+    assert fl.p.numel() == total
+    ref = dict(p=host_f32(fl.p), m=host_f32(fl.m), v=host_f32(fl.v), lp=synth.bits16(fl.p_lp), pdt="bf16")
+    g_host = host_grad(fl.g)
+    ov_ref, ss_ref = oracle.overflow_norm(g_host, "f16", 64.0)
+    c_ref = oracle.clip_coef(ss_ref, float(np.float32(cfg.max_norm)))
+    assert not ov_ref and c_ref < 1
+    ref["lp"] = oracle.adamw_step(ref["p"], ref["m"], ref["v"], g_host, "f16", "bf16", oracle_hyper(cfg), 12, 64.0,
+                                  float(c_ref))
+    plan = ma.MultiPlan(ls.p, ls.m, ls.v, ls.g, ls.p_lp)
+    assert plan.total == total and plan.plan.entries == sum(1 for k in sizes if k > 0)
+    ws, res = ma.workspace(), ma.new_result()
+    ma.multi_overflow_norm(plan, 64.0, res, ws)
+    ma.multi_adamw_step_gated(plan, _hyper(cfg), 12, 64.0, res, cfg.max_norm)
+    ov, ss = ma.read_result(res)
+    assert not ov and abs(ss - ss_ref) <= 1e-11 * ss_ref          # per-tensor partial sums: another order than the oracle's
+    assert np.float32(ma.clip_coef(ss, cfg.max_norm)) == c_ref
+    got = dict(p=host_f32(fl.p), m=host_f32(fl.m), v=host_f32(fl.v), lp=synth.bits16(fl.p_lp))
+    assert_state_close(got, ref, "20,000 tiny tensors")
+    for k in ("p", "m", "v"):
+        assert np.array_equal(got[k].view(np.uint32), ref[k].view(np.uint32)), k
+    # the whole-step call over the same plan, and a NaN in a one-element tensor skipping everything
+    ma.multi_optimizer_step(plan, _hyper(cfg), 13, 64.0, cfg.max_norm, res, ws)
+    ref["lp"] = oracle.adamw_step(ref["p"], ref["m"], ref["v"], g_host, "f16", "bf16", oracle_hyper(cfg), 13, 64.0,
+                                  float(c_ref))
+    assert_state_close(dict(p=host_f32(fl.p), m=host_f32(fl.m), v=host_f32(fl.v), lp=synth.bits16(fl.p_lp)), ref,
+                       "second step, one call")
+    one = next(i for i, k in enumerate(sizes) if k == 1)
+    ls.g[one].view(torch.int16)[0] = 0x7E00
+    before = fl.arena.cpu().numpy().tobytes()
+    ma.multi_optimizer_step(plan, _hyper(cfg), 14, 64.0, cfg.max_norm, res, ws)
+    assert ma.read_result(res)[0] is True and fl.arena.cpu().numpy().tobytes() == before
+
+
 def test_randomised_tensor_lists():
     """40 seeded random tensor lists: 1 to 40 tensors of 0 to 60,000 elements, each of the five buffers
     of each tensor at its own element offset (so rows with every combination of packet-path and
