@@ -63,6 +63,8 @@ MEASURED_TRAFFIC = {      # workload: (bytes per launch, sources, their digest w
     "qwen14b_4sub": (87973259267, STEP_SOURCES, STEP_SHA256),
     "bf16_states_8b": (112423952863, STEP_SOURCES, STEP_SHA256),
     "accumulate_8b": (80301678360, ACCUM_SOURCES, ACCUM_SHA256),
+    "iteration_8b": (240908599968, STEP_SOURCES, STEP_SHA256),
+    "share8_8b": (28105993608, STEP_SOURCES, STEP_SHA256),
     "accumulate1_8b": (48182763199, ACCUM_SOURCES, ACCUM_SHA256),
 }
 
@@ -76,6 +78,8 @@ TRAFFIC_SOURCE = {
     "qwen14b_4sub": "profiles/step_and_norm_flat_kernels__qwen14b_4sub.txt",
     "bf16_states_8b": "profiles/step_flat_kernel_bf16_states__bf16_states_8b.txt",
     "accumulate_8b": "profiles/accumulate_kernel__accumulate_8b.txt",
+    "iteration_8b": "profiles/accumulate_scan_and_step_multi_kernels__iteration_8b.txt",
+    "share8_8b": "profiles/step_and_norm_flat_kernels__share8_8b.txt",
     "accumulate1_8b": "profiles/accumulate_kernel_overwrite_scan__accumulate1_8b.txt",
 }
 
