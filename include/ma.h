@@ -330,7 +330,12 @@ size_t ma_multi_table_bytes(size_t count);
  * copy dtype pdt for the whole list), builds the work table and copies it to table_dev.  This
  * call synchronises `stream` before it returns, so list_host may be freed at once and the table
  * may be used on any stream afterwards.  Prepare once per tensor list; the plan stays valid as
- * long as the tensors do not move.  Tensors with n == 0 are allowed and skipped.  count >= 1. */
+ * long as the tensors do not move.  Tensors with n == 0 are allowed and skipped.  count >= 1.
+ * Every non-empty tensor costs at least one work item (4096 elements' worth of a block's time), so
+ * a list of thousands of tiny tensors runs far below the memory rate (measured: 20,000 tensors of
+ * 0-300 elements, 3.0e6 elements in all, 327 us per step against 25 us for one flat call over the
+ * same bytes; 290 tensors of up to 60,000 elements 76 against 60 us).  When such tensors are views
+ * of one buffer, pass the buffer to the flat calls instead: the step is element-wise. */
 int ma_multi_prepare(const ma_tensor* list_host, size_t count, ma_dtype gdt, ma_dtype pdt,
                      void* table_dev, size_t table_bytes, void* stream, ma_multi_plan* plan_out);
 
