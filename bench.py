@@ -644,6 +644,61 @@ ALSO = (("c1", 400, 40, 32), ("c1_onecall", 400, 40, 32), ("c1_graph", 40, 5, 32
         ("accumulate_8b", 5, 2, 1), ("accumulate1_8b", 8, 2, 1))
 
 
+def extras_of(out, roofline, wl, ma, arena, name, args):
+    """What a default run measures after the timed region (see the module docstring)."""
+    t_extra = time.perf_counter()
+    ceil = mix_ceiling(wl, ma)
+    if ceil is not None:
+        roofline["mix_ceiling_GBps"] = ceil
+        roofline["frac_of_mix_ceiling"] = roofline["achieved"] / ceil
+        log("mix ceiling (%s placement): %.0f GB/s" % (wl.placement, ceil))
+    release(wl)
+    also = out["also"] = []
+    for other, steps, warmup, rotate in ALSO:
+        if other == name:
+            continue
+        w2 = Workload(other, ma, "streams", arena, rotate)
+        ms2 = run(w2, steps, warmup, events_in_region=w2.n >= 10 ** 9)
+        v2, r2, _ = summarise(w2, ma, ms2, quiet=True)
+        also.append({"workload": other, "description": w2.desc, "placement": w2.placement,
+                     "steps": steps, "ms_per_step": ms2, "value": v2,
+                     "kernel_events": "in the timed steps" if w2.n >= 10 ** 9 else "from a second pass",
+                     "unit": "Gparam/s" if w2.kind != "accum" else "G micro-batch elements/s",
+                     "roofline": {k: r2[k] for k in ("kernel", "achieved", "frac", "bytes_per_param",
+                                                     "avg_launch_ms", "first_phase", "traffic")}})
+        if getattr(w2, "graph", None) is not None:
+            also[-1]["sub_group_steps_per_step"] = w2.graph_steps
+            also[-1]["us_per_sub_group_step"] = 1e3 * ms2 / w2.graph_steps
+        if w2.kind in ("bf16", "sub") or (w2.kind == "flat" and w2.n >= 10 ** 7 and getattr(w2, "graph", None) is None):
+            also[-1]["roofline"]["mix_ceiling_GBps"] = mix_ceiling(w2, ma)
+        log("also %-15s %9.4f ms/step  %8.2f %s  dominant kernel %.4f ms = %.0f GB/s (%.1f %%)  mix ceiling %s"
+            % (other, ms2, v2, also[-1]["unit"], r2["avg_launch_ms"], r2["achieved"], 100 * r2["frac"],
+               also[-1]["roofline"].get("mix_ceiling_GBps")))
+        release(w2)
+    if arena is not None:
+        out["check_fp32_by_model"] = check_by_model(ma, arena)
+    if name == "llama3_8b" and arena is not None:
+        # the same list in an ordinary allocation: what a caller sees who does not place the state
+        arena.release()
+        arena = None
+        import gc
+        gc.collect()
+        torch.cuda.empty_cache()
+        w3 = Workload(name, ma, args.layout, None, 1)
+        torch.cuda.synchronize()
+        settle()
+        ms3 = run(w3, 8, 2)
+        v3, r3, _ = summarise(w3, ma, ms3, quiet=True)
+        roofline["frac_plain"] = r3["frac"]
+        roofline["plain"] = {"placement": "plain", "ms_per_step": ms3, "value": v3,
+                             "achieved": r3["achieved"], "avg_launch_ms": r3["avg_launch_ms"],
+                             "mix_ceiling_GBps": mix_ceiling(w3, ma)}
+        log("plain placement: %.3f ms/step, update %.0f GB/s (%.1f %%), mix ceiling %s GB/s"
+            % (ms3, r3["achieved"], 100 * r3["frac"], roofline["plain"]["mix_ceiling_GBps"]))
+        release(w3)
+    log("extras took %.1f s" % (time.perf_counter() - t_extra))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -749,58 +804,12 @@ def main():
     if not args.no_cpu_baseline and wl.kind in ("multi", "flat", "sub"):
         out["cpu_baseline"] = cpu_baseline(wl, args.cpu_sample, args.cpu_passes)
     if extras:
-        t_extra = time.perf_counter()
-        ceil = mix_ceiling(wl, ma)
-        if ceil is not None:
-            roofline["mix_ceiling_GBps"] = ceil
-            roofline["frac_of_mix_ceiling"] = roofline["achieved"] / ceil
-            log("mix ceiling (%s placement): %.0f GB/s" % (wl.placement, ceil))
-        release(wl)
-        also = []
-        for other, steps, warmup, rotate in ALSO:
-            if other == name:
-                continue
-            w2 = Workload(other, ma, "streams", arena, rotate)
-            ms2 = run(w2, steps, warmup, events_in_region=w2.n >= 10 ** 9)
-            v2, r2, _ = summarise(w2, ma, ms2, quiet=True)
-            also.append({"workload": other, "description": w2.desc, "placement": w2.placement,
-                         "steps": steps, "ms_per_step": ms2, "value": v2,
-                         "kernel_events": "in the timed steps" if w2.n >= 10 ** 9 else "from a second pass",
-                         "unit": "Gparam/s" if w2.kind != "accum" else "G micro-batch elements/s",
-                         "roofline": {k: r2[k] for k in ("kernel", "achieved", "frac", "bytes_per_param",
-                                                         "avg_launch_ms", "first_phase", "traffic")}})
-            if getattr(w2, "graph", None) is not None:
-                also[-1]["sub_group_steps_per_step"] = w2.graph_steps
-                also[-1]["us_per_sub_group_step"] = 1e3 * ms2 / w2.graph_steps
-            if w2.kind in ("bf16", "sub") or (w2.kind == "flat" and w2.n >= 10 ** 7 and getattr(w2, "graph", None) is None):
-                also[-1]["roofline"]["mix_ceiling_GBps"] = mix_ceiling(w2, ma)
-            log("also %-15s %9.4f ms/step  %8.2f %s  dominant kernel %.4f ms = %.0f GB/s (%.1f %%)  mix ceiling %s"
-                % (other, ms2, v2, also[-1]["unit"], r2["avg_launch_ms"], r2["achieved"], 100 * r2["frac"],
-                   also[-1]["roofline"].get("mix_ceiling_GBps")))
-            release(w2)
-        out["also"] = also
-        if arena is not None:
-            out["check_fp32_by_model"] = check_by_model(ma, arena)
-        if name == "llama3_8b" and arena is not None:
-            # the same list in an ordinary allocation: what a caller sees who does not place the state
-            arena.release()
-            arena = None
-            import gc
-            gc.collect()
-            torch.cuda.empty_cache()
-            w3 = Workload(name, ma, args.layout, None, 1)
-            torch.cuda.synchronize()
-            settle()
-            ms3 = run(w3, 8, 2)
-            v3, r3, _ = summarise(w3, ma, ms3, quiet=True)
-            roofline["frac_plain"] = r3["frac"]
-            roofline["plain"] = {"placement": "plain", "ms_per_step": ms3, "value": v3,
-                                 "achieved": r3["achieved"], "avg_launch_ms": r3["avg_launch_ms"],
-                                 "mix_ceiling_GBps": mix_ceiling(w3, ma)}
-            log("plain placement: %.3f ms/step, update %.0f GB/s (%.1f %%), mix ceiling %s GB/s"
-                % (ms3, r3["achieved"], 100 * r3["frac"], roofline["plain"]["mix_ceiling_GBps"]))
-            release(w3)
-        log("extras took %.1f s" % (time.perf_counter() - t_extra))
+        # whatever happens in the extras, the line with the headline is printed
+        try:
+            extras_of(out, roofline, wl, ma, arena, name, args)
+        except (Exception, SystemExit) as e:      # noqa: BLE001
+            log("bench.py: the extras stopped early: %r" % (e,))
+            out["extras_error"] = repr(e)
     print(json.dumps(out), flush=True)
 
 
