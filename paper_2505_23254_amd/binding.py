@@ -576,12 +576,17 @@ class Arena:
         _check(lib.ma_arena_create(main_bytes, first_region_bytes, side_bytes, block_bytes,
                                    max_transient_bytes, ctypes.byref(h)))
         self._h = h
-        rep = ArenaReport()
-        _check(lib.ma_arena_get_report(h, ctypes.byref(rep)))
-        self.report = {k: getattr(rep, k) for k, _ in ArenaReport._fields_}
-        self.main = torch.as_tensor(_RawDeviceBytes(lib.ma_arena_main(h), main_bytes, self), device="cuda")
-        self.side = (torch.as_tensor(_RawDeviceBytes(lib.ma_arena_side(h), side_bytes, self), device="cuda")
-                     if side_bytes else None)
+        try:
+            rep = ArenaReport()
+            _check(lib.ma_arena_get_report(h, ctypes.byref(rep)))
+            self.report = {k: getattr(rep, k) for k, _ in ArenaReport._fields_}
+            self.main = torch.as_tensor(_RawDeviceBytes(lib.ma_arena_main(h), main_bytes, self), device="cuda")
+            self.side = (torch.as_tensor(_RawDeviceBytes(lib.ma_arena_side(h), side_bytes, self), device="cuda")
+                         if side_bytes else None)
+        except Exception:
+            lib.ma_arena_destroy(h)      # nothing refers to the range yet
+            self._h = None
+            raise
 
     def close(self):
         if self._h:
